@@ -1,0 +1,251 @@
+/*
+ * CPU oracle for the PWLQ breakpoint search and quantizer.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, literal statement of what
+ * the GPU library must compute.  It shares no code with the HIP path and must
+ * never be called from it; only the tests, the smoke check and the benchmark's
+ * cpu_baseline leg load it.
+ *
+ * What it follows (Fang et al., "Post-Training Piecewise Linear Quantization
+ * for Deep Neural Networks"):
+ *   - Eq.1 (Section 3.1): uniform quantizer  r_q = round((clamp(r) - z)/s),
+ *     r_hat = s*r_q + z,  s = (r_u - r_l)/(N - 1).
+ *   - Eq.3 (Section 3.2): the b-bit piecewise quantizer applies a (b-1)-bit
+ *     uniform quantizer to |r| on [0,p] (offset 0) in the centre region
+ *     R1 = [-p,p] and on [p,m] (offset p) in the tail region R2, then restores
+ *     the sign; the error is  eps = pw(r) - r.
+ *   - Eq.7 (Section 3.3): p* = argmin_p E(eps^2).  Here the expectation is the
+ *     empirical sum of squared errors of the group, and the argmin runs over
+ *     the uniform grid p_k = m*k/n, k = 1..n  (the numerical curve of Fig.1,
+ *     right).
+ *   - Section 4: one extra stored bit per weight names the region.
+ *
+ * Readings where the paper is silent (all listed in the design notes):
+ *   - each piece has N = 2^(b-1) levels, codes 0..L with L = 2^(b-1)-1 (the
+ *     unsigned domain with z = r_l of Section 3.1), so s = range/L;
+ *   - round is round-half-to-even;
+ *   - the code is decided in IEEE binary32, by multiplying with the binary32
+ *     reciprocal of the step, no fused operations;
+ *   - the squared error is accumulated in binary64, in index order;
+ *   - ties in the argmin go to the smallest k;
+ *   - the top code of a piece decodes to the exact end point (p or m).
+ *
+ * Build: gcc -O2 -std=c11 -ffp-contract=off -fopenmp -shared -fPIC
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { REF_OK = 0, REF_EINVAL = 1, REF_ENULL = 2 };
+enum { REF_PER_CHANNEL = 0, REF_PER_TENSOR = 1 };
+
+/* Parameters of the two pieces for one (m, p) pair.  Eq.1: s = Delta/(N-1). */
+typedef struct {
+    float p, m;
+    float s1, s2; /* step of the centre piece [0,p] and of the tail piece [p,m] */
+    float i1, i2; /* binary32 reciprocals of the steps (0 when the step is 0)   */
+    float L;      /* highest code of a piece, 2^(b-1) - 1                        */
+} pieces;
+
+static pieces make_pieces(float m, float p, int bits)
+{
+    pieces q;
+    q.m = m;
+    q.p = p;
+    q.L = (float)((1 << (bits - 1)) - 1);
+    q.s1 = p / q.L;
+    float width2 = m - p;
+    q.s2 = width2 / q.L;
+    q.i1 = (q.s1 > 0.0f) ? 1.0f / q.s1 : 0.0f;
+    q.i2 = (q.s2 > 0.0f) ? 1.0f / q.s2 : 0.0f;
+    return q;
+}
+
+/* Eq.3 on one magnitude a = |r|: which region, which code.  R1 is closed
+ * (a <= p), R2 is (p, m].  Returns the code; *tail receives the region. */
+static float piece_code(const pieces *q, float a, int *tail)
+{
+    float t;
+    if (a > q->p) {
+        *tail = 1;
+        float x = a - q->p; /* clamp(r) - z with z = p */
+        t = x * q->i2;
+    } else {
+        *tail = 0;
+        t = a * q->i1;      /* z = 0 */
+    }
+    float code = rintf(t);  /* round half to even */
+    if (code > q->L) code = q->L; /* saturation to the integer domain */
+    return code;
+}
+
+/* eps = r_hat - r on the magnitude, in binary64 from the binary32 step,
+ * offset, code and magnitude:  s*r_q + z - a. */
+static double piece_error(const pieces *q, float a)
+{
+    int tail;
+    float code = piece_code(q, a, &tail);
+    double s = tail ? (double)q->s2 : (double)q->s1;
+    double z = tail ? (double)q->p : 0.0;
+    return (double)code * s + z - (double)a;
+}
+
+static float grid_point(float m, int k, int n)
+{
+    float ratio = (float)k / (float)n;
+    return m * ratio;
+}
+
+static float group_absmax(const float *w, int64_t count)
+{
+    float m = 0.0f;
+    for (int64_t i = 0; i < count; ++i) {
+        float a = fabsf(w[i]);
+        if (a > m || isnan(a)) m = a;
+        if (isnan(m)) break;
+    }
+    return m;
+}
+
+/* One group: SSE[k-1] for k = 1..n written to curve (length n). */
+static void group_curve_range(const float *w, int64_t count, float m, int bits,
+                              int n, int k_lo, int k_hi, double *curve)
+{
+    for (int k = k_lo; k <= k_hi; ++k) {
+        pieces q = make_pieces(m, grid_point(m, k, n), bits);
+        double sse = 0.0;
+        for (int64_t i = 0; i < count; ++i) {
+            double e = piece_error(&q, fabsf(w[i]));
+            sse += e * e;
+        }
+        curve[k - 1] = sse;
+    }
+}
+
+static void group_pick(const double *curve, int n, float m, int64_t count,
+                       float *p_star, int32_t *k_star, double *mse)
+{
+    int best = 1;
+    for (int k = 2; k <= n; ++k)
+        if (curve[k - 1] < curve[best - 1]) best = k; /* strict: smallest k wins ties */
+    *k_star = best;
+    *p_star = grid_point(m, best, n);
+    *mse = curve[best - 1] / (double)count;
+}
+
+static int check_common(int64_t C, int64_t K, int bits, int mode)
+{
+    if (C < 1 || K < 1) return REF_EINVAL;
+    if (bits < 2 || bits > 8) return REF_EINVAL;
+    if (mode != REF_PER_CHANNEL && mode != REF_PER_TENSOR) return REF_EINVAL;
+    return REF_OK;
+}
+
+/*
+ * w: host [C,K] row-major binary32.  G = C groups (per-channel) or 1
+ * (per-tensor).  Outputs are host arrays of length G; sse_curve (optional,
+ * may be NULL) is [G, n_cand] binary64 and receives every candidate's SSE.
+ * k_star is 1-based.  A group whose absmax is not finite gets k_star = -1 and
+ * NaN for p_star and mse.
+ */
+int pwlq_ref_search(const float *w, int64_t C, int64_t K, int bits, int n_cand,
+                    int mode, float *p_star, float *m_out, int32_t *k_star,
+                    double *mse, double *sse_curve)
+{
+    if (!w || !p_star || !m_out || !k_star || !mse) return REF_ENULL;
+    int rc = check_common(C, K, bits, mode);
+    if (rc) return rc;
+    if (n_cand < 1 || n_cand > 65535) return REF_EINVAL;
+
+    if (mode == REF_PER_CHANNEL) {
+        int failed = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+        for (int64_t g = 0; g < C; ++g) {
+            const float *row = w + g * K;
+            float m = group_absmax(row, K);
+            m_out[g] = m;
+            double *curve = sse_curve ? sse_curve + g * (int64_t)n_cand
+                                      : (double *)malloc(sizeof(double) * (size_t)n_cand);
+            if (!curve) { failed = 1; continue; }
+            if (!isfinite(m)) {
+                k_star[g] = -1; p_star[g] = NAN; mse[g] = NAN;
+                for (int k = 0; k < n_cand; ++k) curve[k] = NAN;
+            } else {
+                group_curve_range(row, K, m, bits, n_cand, 1, n_cand, curve);
+                group_pick(curve, n_cand, m, K, &p_star[g], &k_star[g], &mse[g]);
+            }
+            if (!sse_curve) free(curve);
+        }
+        return failed ? REF_EINVAL : REF_OK;
+    }
+
+    /* per-tensor: one group of C*K elements; candidates are independent, so
+     * the loop over them is the parallel one and every sum stays in index
+     * order. */
+    int64_t count = C * K;
+    float m = group_absmax(w, count);
+    m_out[0] = m;
+    double *curve = sse_curve ? sse_curve : (double *)malloc(sizeof(double) * (size_t)n_cand);
+    if (!curve) return REF_EINVAL;
+    if (!isfinite(m)) {
+        k_star[0] = -1; p_star[0] = NAN; mse[0] = NAN;
+        for (int k = 0; k < n_cand; ++k) curve[k] = NAN;
+    } else {
+#pragma omp parallel for schedule(dynamic, 1)
+        for (int k = 1; k <= n_cand; ++k)
+            group_curve_range(w, count, m, bits, n_cand, k, k, curve);
+        group_pick(curve, n_cand, m, count, &p_star[0], &k_star[0], &mse[0]);
+    }
+    if (!sse_curve) free(curve);
+    return REF_OK;
+}
+
+/*
+ * Quantize with given (m, p) per group.  codes: b-bit sign-magnitude in a
+ * byte (sign in bit b-1, piece code in bits 0..b-2); flags: 0 centre, 1 tail
+ * (Section 4's region bit); w_hat: sign * (s*code + z) in binary32, with the
+ * top code of a piece decoding to the piece's end point.
+ */
+int pwlq_ref_quantize(const float *w, int64_t C, int64_t K, int bits, int mode,
+                      const float *p_star, const float *m_in, uint8_t *codes,
+                      uint8_t *flags, float *w_hat)
+{
+    if (!w || !p_star || !m_in || !codes || !flags || !w_hat) return REF_ENULL;
+    int rc = check_common(C, K, bits, mode);
+    if (rc) return rc;
+
+#pragma omp parallel for schedule(static)
+    for (int64_t g = 0; g < C; ++g) {
+        int64_t gi = (mode == REF_PER_CHANNEL) ? g : 0;
+        pieces q = make_pieces(m_in[gi], p_star[gi], bits);
+        for (int64_t j = 0; j < K; ++j) {
+            int64_t i = g * K + j;
+            float r = w[i];
+            int tail;
+            float code = piece_code(&q, fabsf(r), &tail);
+            float v;
+            if (tail)
+                v = (code == q.L) ? q.m : fmaf(code, q.s2, q.p);
+            else
+                v = (code == q.L) ? q.p : code * q.s1;
+            int neg = (r < 0.0f) && (v > 0.0f);
+            w_hat[i] = neg ? -v : v;
+            flags[i] = (uint8_t)tail;
+            codes[i] = (uint8_t)((int)code | (neg << (bits - 1)));
+        }
+    }
+    return REF_OK;
+}
+
+int pwlq_ref_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

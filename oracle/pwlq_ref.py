@@ -1,0 +1,112 @@
+"""ctypes loader for the CPU oracle (``pwlq_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by the smoke check and by
+the benchmark's cpu_baseline leg.  The product package never imports this
+module, and this module never imports the product's HIP binding.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "pwlq_oracle.c")
+_LIB = os.path.join(_HERE, "libpwlq_ref.so")
+
+PER_CHANNEL = 0
+PER_TENSOR = 1
+
+CFLAGS = ["-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
+          "-shared", "-fPIC", "-Wall", "-Wextra"]
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc.  Returns the path of the shared object."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", *CFLAGS, _SRC, "-o", _LIB, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        fp = ctypes.POINTER(ctypes.c_float)
+        dp = ctypes.POINTER(ctypes.c_double)
+        ip = ctypes.POINTER(ctypes.c_int32)
+        bp = ctypes.POINTER(ctypes.c_uint8)
+        L.pwlq_ref_search.restype = ctypes.c_int
+        L.pwlq_ref_search.argtypes = [fp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
+                                      ctypes.c_int, ctypes.c_int, fp, fp, ip, dp, dp]
+        L.pwlq_ref_quantize.restype = ctypes.c_int
+        L.pwlq_ref_quantize.argtypes = [fp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
+                                        ctypes.c_int, fp, fp, bp, bp, fp]
+        L.pwlq_ref_num_threads.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _ptr(a: np.ndarray, ctype):
+    return a.ctypes.data_as(ctypes.POINTER(ctype))
+
+
+def num_threads() -> int:
+    return int(lib().pwlq_ref_num_threads())
+
+
+def search(w: np.ndarray, bits: int, n_cand: int, mode: int = PER_CHANNEL,
+           want_curve: bool = False):
+    """w: [C, K] float32.  Returns dict(p_star, m, k_star, mse[, curve])."""
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    if w.ndim != 2:
+        raise ValueError("w must be [C, K]")
+    C, K = w.shape
+    G = C if mode == PER_CHANNEL else 1
+    p_star = np.empty(G, np.float32)
+    m = np.empty(G, np.float32)
+    k_star = np.empty(G, np.int32)
+    mse = np.empty(G, np.float64)
+    curve = np.empty((G, n_cand), np.float64) if want_curve else None
+    rc = lib().pwlq_ref_search(
+        _ptr(w, ctypes.c_float), C, K, bits, n_cand, mode,
+        _ptr(p_star, ctypes.c_float), _ptr(m, ctypes.c_float),
+        _ptr(k_star, ctypes.c_int32), _ptr(mse, ctypes.c_double),
+        _ptr(curve, ctypes.c_double) if want_curve else None)
+    if rc != 0:
+        raise ValueError(f"pwlq_ref_search status {rc}")
+    out = dict(p_star=p_star, m=m, k_star=k_star, mse=mse)
+    if want_curve:
+        out["curve"] = curve
+    return out
+
+
+def quantize(w: np.ndarray, bits: int, p_star: np.ndarray, m: np.ndarray,
+             mode: int = PER_CHANNEL) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Returns (codes u8, flags u8, w_hat f32), each shaped like w."""
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    C, K = w.shape
+    G = C if mode == PER_CHANNEL else 1
+    p_star = np.ascontiguousarray(p_star, dtype=np.float32)
+    m = np.ascontiguousarray(m, dtype=np.float32)
+    if p_star.shape != (G,) or m.shape != (G,):
+        raise ValueError("p_star and m must have one entry per group")
+    codes = np.empty((C, K), np.uint8)
+    flags = np.empty((C, K), np.uint8)
+    w_hat = np.empty((C, K), np.float32)
+    rc = lib().pwlq_ref_quantize(
+        _ptr(w, ctypes.c_float), C, K, bits, mode,
+        _ptr(p_star, ctypes.c_float), _ptr(m, ctypes.c_float),
+        _ptr(codes, ctypes.c_uint8), _ptr(flags, ctypes.c_uint8),
+        _ptr(w_hat, ctypes.c_float))
+    if rc != 0:
+        raise ValueError(f"pwlq_ref_quantize status {rc}")
+    return codes, flags, w_hat
