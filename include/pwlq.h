@@ -1,0 +1,137 @@
+/*
+ * pwlq.h - C ABI of libpwlq: optimal-breakpoint search and quantizer of
+ * Post-Training Piecewise Linear Quantization (Fang et al.) on one MI355X.
+ *
+ * Conventions for every call
+ *   - Weight tensors are contiguous, row-major [C, K] binary32 in DEVICE
+ *     memory; a conv weight [Cout, Cin, kh, kw] is passed with K = Cin*kh*kw.
+ *     "Per channel" means per output channel (Section 2, Section 5).
+ *   - A group is one row (PWLQ_PER_CHANNEL) or the whole tensor
+ *     (PWLQ_PER_TENSOR, the paper's "per-layer", Section 5.2).
+ *   - All array arguments except tensor-descriptor tables are DEVICE pointers
+ *     owned by the caller.  The library allocates nothing; scratch comes from
+ *     the caller's workspace.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
+ *     default stream) and the call returns without waiting for it.  Tensor
+ *     descriptor tables are HOST arrays and are consumed before the call
+ *     returns.
+ *   - Return value: a pwlq_status.  On any status other than PWLQ_OK nothing
+ *     was enqueued and no output is written; pwlq_last_error() describes it.
+ *   - Valid ranges: 2 <= bits <= 8, 1 <= n_cand <= 65535, C >= 1, K >= 1,
+ *     at most 2^31-1 elements per group's tile set and per call 2^31-1 tiles.
+ *   - A group whose absmax is NaN or infinite gets k_star = -1 and NaN in
+ *     p_star and mse; quantizing such a group is unspecified.  Groups whose
+ *     absmax is below 2^-100 or above 2^100 are outside the tested domain.
+ */
+#ifndef PWLQ_H
+#define PWLQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PWLQ_OK = 0,
+    PWLQ_EINVAL = 1,     /* argument out of range                     */
+    PWLQ_ENULL = 2,      /* a required pointer is NULL                */
+    PWLQ_EWORKSPACE = 3, /* workspace missing, misaligned or too small */
+    PWLQ_EHIP = 4        /* a HIP runtime call failed                 */
+} pwlq_status;
+
+typedef enum { PWLQ_PER_CHANNEL = 0, PWLQ_PER_TENSOR = 1 } pwlq_mode;
+
+/* One tensor of a model-level call.  w: device [C,K].  group_offset: index of
+ * this tensor's first group in the per-group arrays.  elem_offset: index of
+ * this tensor's first element in the per-element output arrays. */
+typedef struct {
+    const float *w;
+    int64_t C, K;
+    int64_t group_offset;
+    int64_t elem_offset;
+} pwlq_tensor_desc;
+
+/*
+ * Breakpoint search: Eq.7 (Section 3.3) solved on the group's own values.
+ * For each group, m = max|w| and, for k = 1..n_cand, p_k = m*(k/n_cand); the
+ * squared error of the b-bit piecewise quantizer of Eq.3 (Section 3.2: centre
+ * [-p,p] and tails +-(p,m], each piece a (b-1)-bit uniform quantizer of Eq.1
+ * with 2^(b-1) levels) is summed over the group, and the smallest k attaining
+ * the minimum is returned.
+ *
+ * Outputs, device arrays of G entries (G = C per channel, 1 per tensor):
+ *   p_star  the chosen breakpoint p_{k*}
+ *   m_out   the group's absmax
+ *   k_star  1-based index of the chosen candidate
+ *   mse     SSE[k*] / (elements in the group), accumulated in binary64
+ * workspace: device memory, 256-byte aligned, at least
+ * pwlq_search_workspace_bytes(...) bytes; contents are scratch.
+ */
+size_t pwlq_search_workspace_bytes(int64_t C, int64_t K, int bits, int n_cand, int mode);
+
+int pwlq_search(const float *w, int64_t C, int64_t K, int bits, int n_cand, int mode,
+                float *p_star, float *m_out, int32_t *k_star, double *mse,
+                void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Quantizer: Eq.3 with given (m, p) per group.  Device outputs of C*K entries:
+ *   codes  b-bit sign-magnitude in one byte: bit b-1 is the sign, bits 0..b-2
+ *          the piece's code 0..2^(b-1)-1 (Section 3.2: b bits including sign)
+ *   flags  0 = centre region, 1 = tail region (the extra stored bit of
+ *          Section 4)
+ *   w_hat  sign * (step*code + offset) in binary32; the top code of a piece
+ *          decodes to the piece's end point (p or m) exactly; zero is +0
+ * Values with |w| > m are clamped (Eq.1) to the top tail code.
+ */
+int pwlq_quantize(const float *w, int64_t C, int64_t K, int bits, int mode,
+                  const float *p_star, const float *m, uint8_t *codes, uint8_t *flags,
+                  float *w_hat, void *stream);
+
+/*
+ * Model-level variants: every tensor of `desc` (host array of n_tensors
+ * entries) in one set of launches.  Per-group arrays are indexed by
+ * group_offset (+ row, per channel); per-element arrays by elem_offset + the
+ * element's row-major index.  The caller chooses offsets so that tensors do
+ * not overlap.  Semantics per tensor are those of pwlq_search / pwlq_quantize.
+ */
+size_t pwlq_search_list_workspace_bytes(const pwlq_tensor_desc *desc, int n_tensors,
+                                        int bits, int n_cand, int mode);
+
+int pwlq_search_list(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand,
+                     int mode, float *p_star, float *m_out, int32_t *k_star, double *mse,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+size_t pwlq_quantize_list_workspace_bytes(const pwlq_tensor_desc *desc, int n_tensors,
+                                          int bits, int mode);
+
+int pwlq_quantize_list(const pwlq_tensor_desc *desc, int n_tensors, int bits, int mode,
+                       const float *p_star, const float *m, uint8_t *codes, uint8_t *flags,
+                       float *w_hat, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Text of the calling thread's last non-OK status ("" if none).  The storage
+ * is thread-local and owned by the library. */
+const char *pwlq_last_error(void);
+
+/* Counters of the last pwlq_search* call enqueued by the calling thread, for
+ * benchmarks: number of tiles, groups and work units.  Any pointer may be NULL. */
+void pwlq_last_search_shape(int64_t *n_tiles, int64_t *n_groups, int64_t *n_units);
+
+/* Benchmark aid.  With profiling enabled every search / quantize call records
+ * HIP events on its own stream right before and after its dominant kernel
+ * (role 0: the candidate-evaluation kernel of a search; role 1: the quantize
+ * kernel).  pwlq_profile_last_ms waits for the later event of the most recent
+ * call and returns the kernel's duration in milliseconds, or -1 if none was
+ * recorded.  Process-wide, not thread-safe; off by default. */
+void pwlq_profile_enable(int on);
+double pwlq_profile_last_ms(int role);
+
+/* Name of the library's kernels as they appear in a kernel trace, by role:
+ * 0 search (dominant), 1 quantize.  Returns NULL for other roles. */
+const char *pwlq_kernel_name(int role);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PWLQ_H */

@@ -1,0 +1,49 @@
+"""Builds libpwlq.so (HIP, gfx950) in-tree with hipcc."""
+from __future__ import annotations
+
+import os
+import shutil
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libpwlq.so")
+SOURCES = [os.path.join(CSRC, "pwlq_api.hip")]
+HEADERS = [os.path.join(CSRC, "pwlq_device.h"), os.path.join(CSRC, "pwlq_kernels.h"),
+           os.path.join(os.path.dirname(HERE), "include", "pwlq.h")]
+
+# -ffp-contract=off: the canonical code arithmetic must not be fused; fused
+# operations are written explicitly where wanted.  Packed binary32 VALU forms
+# are disabled for the device compile.
+HIPCC_FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "-ffp-contract=off", "-fno-fast-math",
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-Wall", "-Wno-unused-function",
+]
+
+
+def hipcc() -> str:
+    for cand in (shutil.which("hipcc"), "/opt/rocm/bin/hipcc"):
+        if cand and os.path.exists(cand):
+            return cand
+    raise RuntimeError("hipcc not found")
+
+
+def stale() -> bool:
+    if not os.path.exists(LIB):
+        return True
+    t = os.path.getmtime(LIB)
+    return any(os.path.getmtime(p) > t for p in SOURCES + HEADERS)
+
+
+def build(force: bool = True, extra=()) -> str:
+    if force or stale():
+        cmd = [hipcc(), *HIPCC_FLAGS, *extra, *SOURCES, "-o", LIB]
+        subprocess.run(cmd, check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(True, sys.argv[1:]))

@@ -1,0 +1,391 @@
+// Host side of libpwlq: argument checks, the per-call tensor table, workspace
+// layout and kernel launches.  See include/pwlq.h for the contract.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <numeric>
+#include <vector>
+
+#include "../../include/pwlq.h"
+#include "pwlq_kernels.h"
+
+namespace {
+
+using namespace pwlq;
+
+thread_local char g_error[512] = "";
+thread_local long long g_last_tiles = 0, g_last_groups = 0, g_last_units = 0;
+
+int fail(int status, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof(g_error), fmt, ap);
+    va_end(ap);
+    return status;
+}
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Everything a call needs to know about its tensors, built on the host.
+struct Plan {
+    std::vector<TensorRec> recs;
+    std::vector<int> tile_prefix, group_prefix, unit_prefix, mgroup_prefix;
+    int nt = 0;
+    long long n_tiles = 0, n_groups = 0, n_units = 0, n_mgroups = 0, n_part_tiles = 0;
+    long long sorted_elems = 0;
+    int n = 0, nblk = 0, nwords = 0;
+    // workspace offsets in bytes
+    size_t off_recs = 0, off_prefix = 0, off_tile_max = 0, off_gm = 0, off_offsets = 0,
+           off_sorted = 0, off_sse32 = 0, off_mask = 0, off_part = 0, total = 0;
+};
+
+int check_common(int bits, int mode)
+{
+    if (bits < 2 || bits > 8) return fail(PWLQ_EINVAL, "bits=%d outside [2,8]", bits);
+    if (mode != PWLQ_PER_CHANNEL && mode != PWLQ_PER_TENSOR)
+        return fail(PWLQ_EINVAL, "mode=%d is neither PWLQ_PER_CHANNEL nor PWLQ_PER_TENSOR", mode);
+    return PWLQ_OK;
+}
+
+// n_cand == 0 builds a quantize-only plan (no search scratch).
+int build_plan(Plan &pl, const pwlq_tensor_desc *desc, int n_tensors, int n_cand, int mode,
+               bool need_pointers)
+{
+    if (!desc) return fail(PWLQ_ENULL, "tensor descriptor table is NULL");
+    if (n_tensors < 1) return fail(PWLQ_EINVAL, "n_tensors=%d must be >= 1", n_tensors);
+    pl.nt = n_tensors;
+    pl.n = n_cand;
+    pl.nblk = (n_cand + kBlk - 1) / kBlk;
+    pl.nwords = (n_cand + 31) / 32;
+
+    struct Item { int idx; int tile_len; };
+    std::vector<Item> order(n_tensors);
+    std::vector<TensorRec> tmp(n_tensors);
+    for (int i = 0; i < n_tensors; ++i) {
+        const pwlq_tensor_desc &d = desc[i];
+        if (need_pointers && !d.w) return fail(PWLQ_ENULL, "desc[%d].w is NULL", i);
+        if (d.C < 1 || d.K < 1) return fail(PWLQ_EINVAL, "desc[%d]: C=%lld K=%lld must be >= 1", i,
+                                            (long long)d.C, (long long)d.K);
+        if (d.group_offset < 0 || d.elem_offset < 0)
+            return fail(PWLQ_EINVAL, "desc[%d]: negative offset", i);
+        if (d.C > (1LL << 40) / d.K) return fail(PWLQ_EINVAL, "desc[%d]: tensor too large", i);
+        TensorRec r;
+        memset(&r, 0, sizeof(r));
+        r.w = d.w;
+        const long long groups = (mode == PWLQ_PER_CHANNEL) ? d.C : 1;
+        r.gcount = (mode == PWLQ_PER_CHANNEL) ? d.K : d.C * d.K;
+        r.out_elem = d.elem_offset;
+        r.out_group = d.group_offset;
+        const long long tpg = (r.gcount + kTileMax - 1) / kTileMax;
+        r.tile_len = (tpg == 1) ? (int)r.gcount : kTileMax;
+        r.last_len = (int)(r.gcount - (tpg - 1) * (long long)r.tile_len);
+        if (groups * tpg > 0x3fffffffLL) return fail(PWLQ_EINVAL, "desc[%d]: too many tiles", i);
+        r.tpg = (int)tpg;
+        r.ngroups = (int)groups;
+        r.ntiles = (int)(groups * tpg);
+        r.stride = (r.tile_len + kVec - 1) / kVec * kVec + kVec;
+        r.tpu = std::max(1, kUnitElems / r.tile_len);
+        tmp[i] = r;
+        order[i] = {i, r.tile_len};
+    }
+    // longest tiles first: the search kernel's workgroups are dispatched in
+    // index order, so the big items start early and the small ones fill gaps
+    std::stable_sort(order.begin(), order.end(),
+                     [](const Item &a, const Item &b) { return a.tile_len > b.tile_len; });
+    pl.recs.resize(n_tensors);
+    pl.tile_prefix.assign(n_tensors + 1, 0);
+    pl.group_prefix.assign(n_tensors + 1, 0);
+    pl.unit_prefix.assign(n_tensors + 1, 0);
+    pl.mgroup_prefix.assign(n_tensors + 1, 0);
+    long long tiles = 0, groups = 0, units = 0, mgroups = 0, parts = 0, sorted = 0;
+    for (int s = 0; s < n_tensors; ++s) {
+        TensorRec r = tmp[order[s].idx];
+        r.tile_base = (int)tiles;
+        r.group_base = (int)groups;
+        r.unit_base = (int)units;
+        r.mgroup_base = (int)mgroups;
+        r.sorted_base = sorted;
+        r.part_base = (r.tpg > 1) ? (int)parts : -1;
+        pl.tile_prefix[s] = (int)tiles;
+        pl.group_prefix[s] = (int)groups;
+        pl.unit_prefix[s] = (int)units;
+        pl.mgroup_prefix[s] = (int)mgroups;
+        tiles += r.ntiles;
+        groups += r.ngroups;
+        units += (r.ntiles + r.tpu - 1) / r.tpu;
+        if (r.tpg > 1) { mgroups += r.ngroups; parts += r.ntiles; }
+        sorted += (long long)r.ntiles * r.stride;
+        if (tiles > 0x3fffffffLL || units > 0x3fffffffLL)
+            return fail(PWLQ_EINVAL, "call has too many tiles");
+        pl.recs[s] = r;
+    }
+    pl.tile_prefix[n_tensors] = (int)tiles;
+    pl.group_prefix[n_tensors] = (int)groups;
+    pl.unit_prefix[n_tensors] = (int)units;
+    pl.mgroup_prefix[n_tensors] = (int)mgroups;
+    pl.n_tiles = tiles;
+    pl.n_groups = groups;
+    pl.n_units = units;
+    pl.n_mgroups = mgroups;
+    pl.n_part_tiles = parts;
+    pl.sorted_elems = sorted;
+
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes, 256); return at; };
+    pl.off_recs = take(sizeof(TensorRec) * (size_t)n_tensors);
+    pl.off_prefix = take(sizeof(int) * 4 * (size_t)(n_tensors + 1));
+    if (n_cand > 0) {
+        pl.off_tile_max = take(sizeof(float) * (size_t)tiles);
+        pl.off_gm = take(sizeof(float) * (size_t)groups);
+        pl.off_offsets = take(sizeof(int) * (size_t)tiles * (size_t)(pl.nblk + 1));
+        pl.off_sorted = take(sizeof(float) * (size_t)sorted);
+        pl.off_sse32 = take(sizeof(float) * (size_t)tiles * (size_t)n_cand);
+        pl.off_mask = take(sizeof(uint32_t) * (size_t)groups * (size_t)pl.nwords);
+        pl.off_part = take(sizeof(double) * (size_t)parts * (size_t)n_cand);
+    }
+    pl.total = off;
+    return PWLQ_OK;
+}
+
+int check_workspace(const Plan &pl, const void *workspace, size_t bytes)
+{
+    if (!workspace) return fail(PWLQ_EWORKSPACE, "workspace is NULL (%zu bytes needed)", pl.total);
+    if (((uintptr_t)workspace & 255) != 0)
+        return fail(PWLQ_EWORKSPACE, "workspace is not 256-byte aligned");
+    if (bytes < pl.total)
+        return fail(PWLQ_EWORKSPACE, "workspace holds %zu bytes, %zu needed", bytes, pl.total);
+    return PWLQ_OK;
+}
+
+// Copies the tensor table into the head of the workspace and returns the
+// device-side view.  The host vectors are pageable, so the runtime stages
+// them before hipMemcpyAsync returns.
+int upload_tables(const Plan &pl, char *ws, hipStream_t stream, Tables &tb)
+{
+    memset(&tb, 0, sizeof(tb));
+    tb.nt = pl.nt;
+    tb.n_units = (int)pl.n_units;
+    if (pl.nt == 1) {            // the record travels in the kernel arguments
+        tb.one = pl.recs[0];
+        return PWLQ_OK;
+    }
+    std::vector<int> prefix;
+    prefix.reserve(4 * (size_t)(pl.nt + 1));
+    prefix.insert(prefix.end(), pl.tile_prefix.begin(), pl.tile_prefix.end());
+    prefix.insert(prefix.end(), pl.group_prefix.begin(), pl.group_prefix.end());
+    prefix.insert(prefix.end(), pl.unit_prefix.begin(), pl.unit_prefix.end());
+    prefix.insert(prefix.end(), pl.mgroup_prefix.begin(), pl.mgroup_prefix.end());
+    hipError_t e = hipMemcpyAsync(ws + pl.off_recs, pl.recs.data(),
+                                  sizeof(TensorRec) * (size_t)pl.nt, hipMemcpyHostToDevice, stream);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(ws + pl.off_prefix, prefix.data(), sizeof(int) * prefix.size(),
+                           hipMemcpyHostToDevice, stream);
+    if (e != hipSuccess) return fail(PWLQ_EHIP, "table upload: %s", hipGetErrorString(e));
+    tb.recs = reinterpret_cast<const TensorRec *>(ws + pl.off_recs);
+    const int *p = reinterpret_cast<const int *>(ws + pl.off_prefix);
+    tb.tile_prefix = p;
+    tb.group_prefix = p + (pl.nt + 1);
+    tb.unit_prefix = p + 2 * (pl.nt + 1);
+    tb.mgroup_prefix = p + 3 * (pl.nt + 1);
+    return PWLQ_OK;
+}
+
+int launch_status(const char *what)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(PWLQ_EHIP, "%s: %s", what, hipGetErrorString(e));
+    return PWLQ_OK;
+}
+
+// Optional event timing of the dominant kernels (benchmarks only).
+bool g_profile = false;
+hipEvent_t g_ev[4];
+bool g_ev_made = false;
+bool g_ev_valid[2] = {false, false};
+
+void profile_mark(int idx, hipStream_t stream)
+{
+    if (!g_profile) return;
+    if (!g_ev_made) {
+        for (auto &ev : g_ev) (void)hipEventCreate(&ev);
+        g_ev_made = true;
+    }
+    (void)hipEventRecord(g_ev[idx], stream);
+    if (idx & 1) g_ev_valid[idx >> 1] = true;
+}
+
+int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand, int mode,
+               float *p_star, float *m_out, int32_t *k_star, double *mse, void *workspace,
+               size_t workspace_bytes, void *stream_v)
+{
+    int rc = check_common(bits, mode);
+    if (rc) return rc;
+    if (n_cand < 1 || n_cand > 65535) return fail(PWLQ_EINVAL, "n_cand=%d outside [1,65535]", n_cand);
+    if (!p_star || !m_out || !k_star || !mse) return fail(PWLQ_ENULL, "an output pointer is NULL");
+    Plan pl;
+    rc = build_plan(pl, desc, n_tensors, n_cand, mode, true);
+    if (rc) return rc;
+    rc = check_workspace(pl, workspace, workspace_bytes);
+    if (rc) return rc;
+
+    hipStream_t stream = (hipStream_t)stream_v;
+    char *ws = (char *)workspace;
+    Tables tb;
+    rc = upload_tables(pl, ws, stream, tb);
+    if (rc) return rc;
+    float *tile_max = (float *)(ws + pl.off_tile_max);
+    float *gm = (float *)(ws + pl.off_gm);
+    int *offsets = (int *)(ws + pl.off_offsets);
+    float *sorted = (float *)(ws + pl.off_sorted);
+    float *sse32 = (float *)(ws + pl.off_sse32);
+    uint32_t *mask = (uint32_t *)(ws + pl.off_mask);
+    double *part64 = (double *)(ws + pl.off_part);
+
+    const int NT = (int)pl.n_tiles;
+    k_tile_absmax<<<NT, kWG, 0, stream>>>(tb, tile_max);
+    if (pl.nblk <= 32) {
+        k_prep<true><<<NT, kWG, sizeof(int) * pl.nblk * kWG, stream>>>(
+            tb, n_cand, pl.nblk, tile_max, gm, offsets, sorted);
+    } else {
+        k_prep<false><<<NT, kWG, sizeof(int) * pl.nblk, stream>>>(
+            tb, n_cand, pl.nblk, tile_max, gm, offsets, sorted);
+    }
+    const int ny = (pl.nblk + kWaves - 1) / kWaves;
+    const long long units_padded = (pl.n_units + 7) / 8 * 8;
+    const long long wgs = units_padded * ny;
+    if (wgs > 0x7fffffffLL) return fail(PWLQ_EINVAL, "search grid too large");
+    profile_mark(0, stream);
+    k_search<<<(unsigned)wgs, kWG, 0, stream>>>(tb, n_cand, pl.nblk, bits, (int)units_padded, ny,
+                                                offsets, sorted, sse32);
+    profile_mark(1, stream);
+    k_flag<<<(int)pl.n_groups, kWG, 0, stream>>>(tb, n_cand, pl.nwords, gm, sse32, mask);
+    k_exact<<<NT, kWG, 0, stream>>>(tb, n_cand, pl.nwords, bits, gm, mask, part64, p_star, m_out,
+                                    k_star, mse);
+    if (pl.n_mgroups > 0)
+        k_final<<<(int)pl.n_mgroups, kWG, 0, stream>>>(tb, n_cand, pl.nwords, gm, mask, part64,
+                                                       p_star, m_out, k_star, mse);
+    g_last_tiles = pl.n_tiles;
+    g_last_groups = pl.n_groups;
+    g_last_units = pl.n_units;
+    return launch_status("search launch");
+}
+
+int run_quantize(const pwlq_tensor_desc *desc, int n_tensors, int bits, int mode,
+                 const float *p_star, const float *m, uint8_t *codes, uint8_t *flags, float *w_hat,
+                 void *workspace, size_t workspace_bytes, void *stream_v)
+{
+    int rc = check_common(bits, mode);
+    if (rc) return rc;
+    if (!p_star || !m || !codes || !flags || !w_hat)
+        return fail(PWLQ_ENULL, "an input or output pointer is NULL");
+    Plan pl;
+    rc = build_plan(pl, desc, n_tensors, 0, mode, true);
+    if (rc) return rc;
+    if (pl.nt > 1) {
+        rc = check_workspace(pl, workspace, workspace_bytes);
+        if (rc) return rc;
+    }
+    hipStream_t stream = (hipStream_t)stream_v;
+    Tables tb;
+    rc = upload_tables(pl, (char *)workspace, stream, tb);
+    if (rc) return rc;
+    profile_mark(2, stream);
+    k_emit<<<(int)pl.n_tiles, kWG, 0, stream>>>(tb, bits, p_star, m, codes, flags, w_hat);
+    profile_mark(3, stream);
+    return launch_status("quantize launch");
+}
+
+} // namespace
+
+extern "C" {
+
+size_t pwlq_search_list_workspace_bytes(const pwlq_tensor_desc *desc, int n_tensors, int bits,
+                                        int n_cand, int mode)
+{
+    if (check_common(bits, mode) || n_cand < 1 || n_cand > 65535) return 0;
+    Plan pl;
+    if (build_plan(pl, desc, n_tensors, n_cand, mode, false)) return 0;
+    return pl.total;
+}
+
+size_t pwlq_search_workspace_bytes(int64_t C, int64_t K, int bits, int n_cand, int mode)
+{
+    pwlq_tensor_desc d = {nullptr, C, K, 0, 0};
+    return pwlq_search_list_workspace_bytes(&d, 1, bits, n_cand, mode);
+}
+
+int pwlq_search_list(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand, int mode,
+                     float *p_star, float *m_out, int32_t *k_star, double *mse, void *workspace,
+                     size_t workspace_bytes, void *stream)
+{
+    return run_search(desc, n_tensors, bits, n_cand, mode, p_star, m_out, k_star, mse, workspace,
+                      workspace_bytes, stream);
+}
+
+int pwlq_search(const float *w, int64_t C, int64_t K, int bits, int n_cand, int mode,
+                float *p_star, float *m_out, int32_t *k_star, double *mse, void *workspace,
+                size_t workspace_bytes, void *stream)
+{
+    if (!w) return fail(PWLQ_ENULL, "w is NULL");
+    pwlq_tensor_desc d = {w, C, K, 0, 0};
+    return run_search(&d, 1, bits, n_cand, mode, p_star, m_out, k_star, mse, workspace,
+                      workspace_bytes, stream);
+}
+
+size_t pwlq_quantize_list_workspace_bytes(const pwlq_tensor_desc *desc, int n_tensors, int bits,
+                                          int mode)
+{
+    if (check_common(bits, mode)) return 0;
+    Plan pl;
+    if (build_plan(pl, desc, n_tensors, 0, mode, false)) return 0;
+    return pl.total;
+}
+
+int pwlq_quantize_list(const pwlq_tensor_desc *desc, int n_tensors, int bits, int mode,
+                       const float *p_star, const float *m, uint8_t *codes, uint8_t *flags,
+                       float *w_hat, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return run_quantize(desc, n_tensors, bits, mode, p_star, m, codes, flags, w_hat, workspace,
+                        workspace_bytes, stream);
+}
+
+int pwlq_quantize(const float *w, int64_t C, int64_t K, int bits, int mode, const float *p_star,
+                  const float *m, uint8_t *codes, uint8_t *flags, float *w_hat, void *stream)
+{
+    if (!w) return fail(PWLQ_ENULL, "w is NULL");
+    pwlq_tensor_desc d = {w, C, K, 0, 0};
+    return run_quantize(&d, 1, bits, mode, p_star, m, codes, flags, w_hat, nullptr, 0, stream);
+}
+
+const char *pwlq_last_error(void) { return g_error; }
+
+void pwlq_profile_enable(int on) { g_profile = on != 0; }
+
+double pwlq_profile_last_ms(int role)
+{
+    if (role < 0 || role > 1 || !g_ev_made || !g_ev_valid[role]) return -1.0;
+    float ms = -1.0f;
+    if (hipEventSynchronize(g_ev[2 * role + 1]) != hipSuccess) return -1.0;
+    if (hipEventElapsedTime(&ms, g_ev[2 * role], g_ev[2 * role + 1]) != hipSuccess) return -1.0;
+    return (double)ms;
+}
+
+void pwlq_last_search_shape(int64_t *n_tiles, int64_t *n_groups, int64_t *n_units)
+{
+    if (n_tiles) *n_tiles = g_last_tiles;
+    if (n_groups) *n_groups = g_last_groups;
+    if (n_units) *n_units = g_last_units;
+}
+
+const char *pwlq_kernel_name(int role)
+{
+    if (role == 0) return "k_search";
+    if (role == 1) return "k_emit";
+    return nullptr;
+}
+
+} // extern "C"

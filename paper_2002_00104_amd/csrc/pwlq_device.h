@@ -1,0 +1,151 @@
+// Device-side tables and helpers shared by the libpwlq kernels (gfx950).
+//
+// A call describes its tensors with a small table of TensorRec (one per
+// tensor, sorted by tile length, longest first).  Kernels turn a tile, group
+// or unit index into a tensor with a binary search over a prefix array and
+// derive everything else arithmetically, so no per-tile table is uploaded.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pwlq {
+
+constexpr int kWG = 256;          // threads per workgroup (4 wavefronts of 64)
+constexpr int kWaves = kWG / 64;
+constexpr int kBlk = 64;          // candidates per wavefront: lane = candidate
+constexpr int kTileMax = 8192;    // longest run of a group handled by one workgroup
+constexpr int kUnitElems = 4096;  // small tiles are batched up to about this many elements
+constexpr int kVec = 8;           // elements per scalar vector load in the search loop
+constexpr int kChunk = 128;       // elements per inner fp32 accumulation chunk
+
+struct TensorRec {
+    const float *w;        // device [C, K]
+    long long gcount;      // elements per group
+    long long sorted_base; // first element of this tensor's region in the sorted array
+    long long out_elem;    // caller's elem_offset
+    long long out_group;   // caller's group_offset
+    int tile_len;          // full tile length
+    int last_len;          // length of the last tile of a group
+    int tpg;               // tiles per group
+    int stride;            // padded tile length in the sorted array
+    int tpu;               // tiles per search unit
+    int part_base;         // first partial-sum row (multi-tile groups), else -1
+    int tile_base, group_base, unit_base, mgroup_base;
+    int ntiles, ngroups;
+};
+
+struct TileInfo {
+    const float *src;
+    long long sorted_off;
+    long long elem_off;   // row-major index of the tile's first element in its tensor
+    int len, group, tensor, local_tile, group_local, tile_in_group;
+};
+
+// largest i in [0, nt) with prefix[i] <= x; prefix[nt] > x is required
+__device__ inline int find_tensor(const int *__restrict__ prefix, int nt, int x)
+{
+    int lo = 0, hi = nt;
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (prefix[mid] <= x) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__device__ inline TileInfo tile_info(const TensorRec &r, int tensor, int t)
+{
+    TileInfo ti;
+    ti.tensor = tensor;
+    ti.local_tile = t - r.tile_base;
+    ti.group_local = ti.local_tile / r.tpg;
+    ti.tile_in_group = ti.local_tile - ti.group_local * r.tpg;
+    ti.elem_off = (long long)ti.group_local * r.gcount + (long long)ti.tile_in_group * r.tile_len;
+    ti.src = r.w + ti.elem_off;
+    ti.len = (ti.tile_in_group == r.tpg - 1) ? r.last_len : r.tile_len;
+    ti.group = r.group_base + ti.group_local;
+    ti.sorted_off = r.sorted_base + (long long)ti.local_tile * r.stride;
+    return ti;
+}
+
+// ---- wavefront / workgroup reductions (fixed order, so results are repeatable)
+__device__ inline float wave_max(float v)
+{
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+__device__ inline double wave_sum(double v)
+{
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+__device__ inline double wave_min(double v)
+{
+    for (int off = 32; off > 0; off >>= 1) v = fmin(v, __shfl_xor(v, off, 64));
+    return v;
+}
+__device__ inline int wave_or(int v)
+{
+    for (int off = 32; off > 0; off >>= 1) v |= __shfl_xor(v, off, 64);
+    return v;
+}
+
+// Sum over the workgroup, returned to every thread.  `lds` holds kWaves doubles.
+__device__ inline double block_sum(double v, double *lds)
+{
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = v;
+    __syncthreads();
+    double s = lds[0];
+    for (int i = 1; i < kWaves; ++i) s += lds[i];
+    return s;
+}
+__device__ inline double block_min(double v, double *lds)
+{
+    v = wave_min(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = v;
+    __syncthreads();
+    double s = lds[0];
+    for (int i = 1; i < kWaves; ++i) s = fmin(s, lds[i]);
+    return s;
+}
+
+// ---- the canonical binary32 arithmetic of one (m, p) pair: Eq.1 steps of the
+// centre piece [0,p] and the tail piece [p,m], each with L = 2^(b-1)-1 steps.
+struct Pieces {
+    float p, m, s1, s2, i1, i2, L;
+};
+
+__device__ inline float grid_point(float m, int k, int n)
+{
+    float ratio = (float)k / (float)n;
+    return m * ratio;
+}
+
+__device__ inline Pieces make_pieces(float m, float p, int bits)
+{
+    Pieces q;
+    q.m = m;
+    q.p = p;
+    q.L = (float)((1 << (bits - 1)) - 1);
+    q.s1 = p / q.L;
+    float width = m - p;
+    q.s2 = width / q.L;
+    q.i1 = (q.s1 > 0.0f) ? 1.0f / q.s1 : 0.0f;
+    q.i2 = (q.s2 > 0.0f) ? 1.0f / q.s2 : 0.0f;
+    return q;
+}
+
+// Eq.3 on a magnitude: region (closed centre) and saturated, half-to-even code.
+__device__ inline float piece_code(const Pieces &q, float a, bool &tail)
+{
+    tail = a > q.p;
+    float x = a - q.p;
+    float t = tail ? x * q.i2 : a * q.i1;
+    float code = rintf(t);
+    return (code > q.L) ? q.L : code;
+}
+
+} // namespace pwlq

@@ -1,0 +1,232 @@
+"""ctypes binding over libpwlq.so: argument marshalling only.
+
+Every step of the search and of the quantizer runs in the library's HIP
+kernels; PyTorch is used for device memory and for the current stream.  There
+is no fallback: if the shared library is missing the import of this module
+raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, List, Optional, Sequence
+
+import torch
+
+PER_CHANNEL = 0
+PER_TENSOR = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpwlq.so")
+
+EXPORTS = (
+    "pwlq_search_workspace_bytes", "pwlq_search", "pwlq_quantize",
+    "pwlq_search_list_workspace_bytes", "pwlq_search_list",
+    "pwlq_quantize_list_workspace_bytes", "pwlq_quantize_list",
+    "pwlq_last_error", "pwlq_last_search_shape", "pwlq_profile_enable",
+    "pwlq_profile_last_ms", "pwlq_kernel_name",
+)
+
+
+class TensorDesc(ctypes.Structure):
+    _fields_ = [("w", ctypes.c_void_p), ("C", ctypes.c_int64), ("K", ctypes.c_int64),
+                ("group_offset", ctypes.c_int64), ("elem_offset", ctypes.c_int64)]
+
+
+class PwlqError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"libpwlq status {status}: {text}")
+        self.status = status
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2002_00104_amd.build` "
+            "(there is no CPU fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i64, ci, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
+    dp = ctypes.POINTER(TensorDesc)
+    lib.pwlq_search_workspace_bytes.restype = sz
+    lib.pwlq_search_workspace_bytes.argtypes = [i64, i64, ci, ci, ci]
+    lib.pwlq_search.restype = ci
+    lib.pwlq_search.argtypes = [vp, i64, i64, ci, ci, ci, vp, vp, vp, vp, vp, sz, vp]
+    lib.pwlq_quantize.restype = ci
+    lib.pwlq_quantize.argtypes = [vp, i64, i64, ci, ci, vp, vp, vp, vp, vp, vp]
+    lib.pwlq_search_list_workspace_bytes.restype = sz
+    lib.pwlq_search_list_workspace_bytes.argtypes = [dp, ci, ci, ci, ci]
+    lib.pwlq_search_list.restype = ci
+    lib.pwlq_search_list.argtypes = [dp, ci, ci, ci, ci, vp, vp, vp, vp, vp, sz, vp]
+    lib.pwlq_quantize_list_workspace_bytes.restype = sz
+    lib.pwlq_quantize_list_workspace_bytes.argtypes = [dp, ci, ci, ci]
+    lib.pwlq_quantize_list.restype = ci
+    lib.pwlq_quantize_list.argtypes = [dp, ci, ci, ci, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.pwlq_last_error.restype = ctypes.c_char_p
+    lib.pwlq_last_error.argtypes = []
+    lib.pwlq_last_search_shape.restype = None
+    lib.pwlq_last_search_shape.argtypes = [ctypes.POINTER(i64)] * 3
+    lib.pwlq_profile_enable.restype = None
+    lib.pwlq_profile_enable.argtypes = [ci]
+    lib.pwlq_profile_last_ms.restype = ctypes.c_double
+    lib.pwlq_profile_last_ms.argtypes = [ci]
+    lib.pwlq_kernel_name.restype = ctypes.c_char_p
+    lib.pwlq_kernel_name.argtypes = [ci]
+    return lib
+
+
+lib = _load()
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise PwlqError(status, lib.pwlq_last_error().decode())
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev32(w: torch.Tensor) -> torch.Tensor:
+    if not (w.is_cuda and w.dtype == torch.float32 and w.is_contiguous() and w.dim() == 2):
+        raise ValueError("weights must be a contiguous float32 [C, K] tensor on the GPU")
+    return w
+
+
+def _n_groups(C: int, mode: int) -> int:
+    return C if mode == PER_CHANNEL else 1
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def search_workspace_bytes(C: int, K: int, bits: int, n_cand: int, mode: int) -> int:
+    return int(lib.pwlq_search_workspace_bytes(C, K, bits, n_cand, mode))
+
+
+def search(w: torch.Tensor, bits: int, n_cand: int, mode: int = PER_CHANNEL,
+           workspace: Optional[torch.Tensor] = None) -> Dict[str, torch.Tensor]:
+    """pwlq_search on one [C, K] tensor.  Returns p_star, m, k_star, mse (device)."""
+    w = _dev32(w)
+    C, K = w.shape
+    G = _n_groups(C, mode)
+    if workspace is None:
+        workspace = _workspace(search_workspace_bytes(C, K, bits, n_cand, mode), w.device)
+    out = dict(p_star=torch.empty(G, dtype=torch.float32, device=w.device),
+               m=torch.empty(G, dtype=torch.float32, device=w.device),
+               k_star=torch.empty(G, dtype=torch.int32, device=w.device),
+               mse=torch.empty(G, dtype=torch.float64, device=w.device))
+    _check(lib.pwlq_search(w.data_ptr(), C, K, bits, n_cand, mode, out["p_star"].data_ptr(),
+                           out["m"].data_ptr(), out["k_star"].data_ptr(), out["mse"].data_ptr(),
+                           workspace.data_ptr(), workspace.numel(), _stream()))
+    return out
+
+
+def quantize(w: torch.Tensor, bits: int, p_star: torch.Tensor, m: torch.Tensor,
+             mode: int = PER_CHANNEL):
+    """pwlq_quantize on one [C, K] tensor.  Returns (codes u8, flags u8, w_hat f32)."""
+    w = _dev32(w)
+    C, K = w.shape
+    G = _n_groups(C, mode)
+    for t in (p_star, m):
+        if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.numel() == G):
+            raise ValueError("p_star and m must be float32 device tensors with one entry per group")
+    codes = torch.empty((C, K), dtype=torch.uint8, device=w.device)
+    flags = torch.empty((C, K), dtype=torch.uint8, device=w.device)
+    w_hat = torch.empty((C, K), dtype=torch.float32, device=w.device)
+    _check(lib.pwlq_quantize(w.data_ptr(), C, K, bits, mode, p_star.data_ptr(), m.data_ptr(),
+                             codes.data_ptr(), flags.data_ptr(), w_hat.data_ptr(), _stream()))
+    return codes, flags, w_hat
+
+
+class TensorList:
+    """Descriptor table for the model-level calls: tensors laid out back to back
+    in the per-group and per-element arrays, in the order given."""
+
+    def __init__(self, tensors: Sequence[torch.Tensor], mode: int):
+        self.tensors: List[torch.Tensor] = [_dev32(t) for t in tensors]
+        self.mode = mode
+        self.device = self.tensors[0].device
+        self.desc = (TensorDesc * len(self.tensors))()
+        g = e = 0
+        self.group_offsets: List[int] = []
+        self.elem_offsets: List[int] = []
+        for i, t in enumerate(self.tensors):
+            C, K = t.shape
+            self.desc[i] = TensorDesc(t.data_ptr(), C, K, g, e)
+            self.group_offsets.append(g)
+            self.elem_offsets.append(e)
+            g += _n_groups(C, mode)
+            e += C * K
+        self.n_groups = g
+        self.n_elements = e
+
+    def __len__(self) -> int:
+        return len(self.tensors)
+
+
+def search_list_workspace_bytes(tl: TensorList, bits: int, n_cand: int) -> int:
+    return int(lib.pwlq_search_list_workspace_bytes(tl.desc, len(tl), bits, n_cand, tl.mode))
+
+
+def search_list(tl: TensorList, bits: int, n_cand: int,
+                workspace: Optional[torch.Tensor] = None,
+                out: Optional[Dict[str, torch.Tensor]] = None) -> Dict[str, torch.Tensor]:
+    if workspace is None:
+        workspace = _workspace(search_list_workspace_bytes(tl, bits, n_cand), tl.device)
+    if out is None:
+        out = alloc_search_outputs(tl.n_groups, tl.device)
+    _check(lib.pwlq_search_list(tl.desc, len(tl), bits, n_cand, tl.mode, out["p_star"].data_ptr(),
+                                out["m"].data_ptr(), out["k_star"].data_ptr(),
+                                out["mse"].data_ptr(), workspace.data_ptr(), workspace.numel(),
+                                _stream()))
+    return out
+
+
+def alloc_search_outputs(G: int, device) -> Dict[str, torch.Tensor]:
+    return dict(p_star=torch.empty(G, dtype=torch.float32, device=device),
+                m=torch.empty(G, dtype=torch.float32, device=device),
+                k_star=torch.empty(G, dtype=torch.int32, device=device),
+                mse=torch.empty(G, dtype=torch.float64, device=device))
+
+
+def quantize_list_workspace_bytes(tl: TensorList, bits: int) -> int:
+    return int(lib.pwlq_quantize_list_workspace_bytes(tl.desc, len(tl), bits, tl.mode))
+
+
+def alloc_quantize_outputs(n_elements: int, device):
+    return (torch.empty(n_elements, dtype=torch.uint8, device=device),
+            torch.empty(n_elements, dtype=torch.uint8, device=device),
+            torch.empty(n_elements, dtype=torch.float32, device=device))
+
+
+def quantize_list(tl: TensorList, bits: int, p_star: torch.Tensor, m: torch.Tensor,
+                  workspace: Optional[torch.Tensor] = None, out=None):
+    if workspace is None:
+        workspace = _workspace(quantize_list_workspace_bytes(tl, bits), tl.device)
+    if out is None:
+        out = alloc_quantize_outputs(tl.n_elements, tl.device)
+    codes, flags, w_hat = out
+    _check(lib.pwlq_quantize_list(tl.desc, len(tl), bits, tl.mode, p_star.data_ptr(), m.data_ptr(),
+                                  codes.data_ptr(), flags.data_ptr(), w_hat.data_ptr(),
+                                  workspace.data_ptr(), workspace.numel(), _stream()))
+    return codes, flags, w_hat
+
+
+def profile_enable(on: bool) -> None:
+    lib.pwlq_profile_enable(1 if on else 0)
+
+
+def profile_last_ms(role: int) -> float:
+    return float(lib.pwlq_profile_last_ms(role))
+
+
+def last_search_shape():
+    a, b, c = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+    lib.pwlq_last_search_shape(ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
+    return dict(tiles=a.value, groups=b.value, units=c.value)
+
+
+def kernel_name(role: int) -> Optional[str]:
+    s = lib.pwlq_kernel_name(role)
+    return s.decode() if s else None

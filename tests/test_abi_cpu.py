@@ -1,0 +1,78 @@
+"""Host-side checks that need no GPU: the library loads, exports what the
+header declares, sizes workspaces sensibly and rejects bad arguments before
+touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "pwlq.h")
+LIB = os.path.join(ROOT, "paper_2002_00104_amd", "libpwlq.so")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2002_00104_amd import build
+        build.build(True)
+    return ctypes.CDLL(LIB)
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pwlq_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert {"pwlq_search", "pwlq_quantize", "pwlq_search_list", "pwlq_quantize_list"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_binding_lists_the_same_symbols():
+    import importlib.util
+    spec = importlib.util.find_spec("paper_2002_00104_amd.pwlq")
+    src = open(spec.origin).read()
+    for name in declared_functions():
+        assert f'"{name}"' in src, name
+
+
+def test_workspace_sizes(lib):
+    f = lib.pwlq_search_workspace_bytes
+    f.restype = ctypes.c_size_t
+    f.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+    small = f(64, 576, 4, 100, 0)
+    # at least the rescaled copy of the weights and one binary32 SSE per candidate
+    assert small >= 64 * 576 * 4 + 64 * 100 * 4
+    assert f(38400, 4096, 4, 1000, 0) < 2 * 1024 ** 3
+    assert f(64, 576, 4, 100, 1) > 0
+    for bad in ((0, 5, 4, 10, 0), (5, 0, 4, 10, 0), (5, 5, 1, 10, 0), (5, 5, 9, 10, 0),
+                (5, 5, 4, 0, 0), (5, 5, 4, 70000, 0), (5, 5, 4, 10, 2)):
+        assert f(*bad) == 0, bad
+
+
+def test_bad_arguments_are_rejected_on_the_host(lib):
+    lib.pwlq_last_error.restype = ctypes.c_char_p
+    vp = ctypes.c_void_p
+    lib.pwlq_search.restype = ctypes.c_int
+    lib.pwlq_search.argtypes = [vp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
+                                ctypes.c_int, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    fake = 0x1000  # never dereferenced: every call below fails validation first
+    assert lib.pwlq_search(None, 4, 4, 4, 10, 0, fake, fake, fake, fake, fake, 1 << 20, None) == 2
+    assert lib.pwlq_search(fake, 4, 4, 4, 10, 0, None, fake, fake, fake, fake, 1 << 20, None) == 2
+    assert lib.pwlq_search(fake, 4, 4, 1, 10, 0, fake, fake, fake, fake, fake, 1 << 20, None) == 1
+    assert lib.pwlq_search(fake, 4, 4, 4, 0, 0, fake, fake, fake, fake, fake, 1 << 20, None) == 1
+    assert lib.pwlq_search(fake, 4, 4, 4, 10, 0, fake, fake, fake, fake, None, 0, None) == 3
+    assert lib.pwlq_search(fake, 4, 4, 4, 10, 0, fake, fake, fake, fake, 0x1100, 16, None) == 3
+    assert lib.pwlq_search(fake, 4, 4, 4, 10, 0, fake, fake, fake, fake, 0x1001, 1 << 20, None) == 3
+    assert b"aligned" in lib.pwlq_last_error()
+    lib.pwlq_quantize.restype = ctypes.c_int
+    lib.pwlq_quantize.argtypes = [vp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
+                                  vp, vp, vp, vp, vp, vp]
+    assert lib.pwlq_quantize(fake, 4, 4, 4, 0, None, fake, fake, fake, fake, None) == 2
+    assert lib.pwlq_quantize(fake, 4, 4, 9, 0, fake, fake, fake, fake, fake, None) == 1
+    assert lib.pwlq_quantize(fake, 0, 4, 4, 0, fake, fake, fake, fake, fake, None) == 1

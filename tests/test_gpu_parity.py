@@ -1,0 +1,257 @@
+"""GPU parity: the HIP library against the CPU oracle on the same seeded inputs.
+
+All calls go through the C ABI (ctypes binding).  Small cases are compared
+group by group and element by element; the full-size workloads run on the GPU
+in the benchmark's launch configuration and are compared on sampled groups the
+oracle can compute one by one.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import pwlq_ref as R
+from paper_2002_00104_amd import synth
+from parity import assert_quantize_matches, assert_search_matches
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def P():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2002_00104_amd import pwlq
+    return pwlq
+
+
+def to_np(d):
+    return {k: v.cpu().numpy() for k, v in d.items()}
+
+
+def run_both(P, w, bits, n, mode, what):
+    import torch
+    say(f"[case] {what}: shape={w.shape} bits={bits} n={n} mode={mode}")
+    wd = torch.from_numpy(w).cuda()
+    g = P.search(wd, bits, n, mode)
+    torch.cuda.synchronize()
+    g = to_np(g)
+    r = R.search(w, bits, n, mode, want_curve=True)
+    stats = assert_search_matches(g, r, what)
+    # quantize with the oracle's parameters on both sides, so a legitimate
+    # near-tie difference in k* cannot leak into the code comparison
+    ps, ms = r["p_star"].copy(), r["m"].copy()
+    fin = np.isfinite(ms) & np.isfinite(ps)
+    ps[~fin] = 0.5
+    ms[~fin] = 1.0
+    wq = w.copy()
+    if mode == synth.PER_CHANNEL:
+        wq[~fin] = 0.25
+    elif not fin.all():
+        wq[:] = 0.25
+    q = P.quantize(torch.from_numpy(wq).cuda(), bits, torch.from_numpy(ps).cuda(),
+                   torch.from_numpy(ms).cuda(), mode)
+    torch.cuda.synchronize()
+    q = tuple(t.cpu().numpy() for t in q)
+    assert_quantize_matches(q, R.quantize(wq, bits, ps, ms, mode), what)
+    return stats
+
+
+# ----------------------------------------------------------------- workload 1
+def test_workload1_full(P):
+    wl = synth.workload(1)
+    stats = run_both(P, wl.tensor(0), wl.bits, wl.n_cand, wl.mode, "workload1")
+    say(stats)
+
+
+# ------------------------------------------------------------ shapes and sizes
+@pytest.mark.parametrize("K", [1, 2, 9, 63, 64, 65, 577, 4608, 8191, 8192, 8193, 20000])
+def test_channel_lengths(P, K):
+    rng = np.random.default_rng(K)
+    C = 5 if K > 1000 else 37
+    w = (rng.laplace(0, 0.03, size=(C, K)) * np.exp(rng.normal(0, 1, size=(C, 1)))).astype(np.float32)
+    run_both(P, w, 4, 250, synth.PER_CHANNEL, f"K={K}")
+
+
+@pytest.mark.parametrize("bits", [2, 3, 5, 6, 7, 8])
+def test_bit_widths(P, bits):
+    rng = np.random.default_rng(bits)
+    w = rng.standard_normal((24, 700)).astype(np.float32) * 0.1
+    run_both(P, w, bits, 300, synth.PER_CHANNEL, f"bits={bits}")
+
+
+@pytest.mark.parametrize("n", [1, 2, 7, 63, 64, 65, 128, 129, 1000, 2048, 2049, 5000])
+def test_candidate_counts(P, n):
+    rng = np.random.default_rng(n)
+    w = rng.laplace(0, 0.05, size=(9, 333)).astype(np.float32)
+    run_both(P, w, 4, n, synth.PER_CHANNEL, f"n_cand={n}")
+
+
+@pytest.mark.parametrize("shape,n,bits", [((64, 576), 200, 3), ((37, 1000), 300, 4),
+                                           ((3, 8192), 150, 4), ((1, 100003), 400, 3)])
+def test_per_tensor(P, shape, n, bits):
+    rng = np.random.default_rng(shape[1])
+    w = (0.02 * rng.standard_t(3.0, size=shape)).astype(np.float32)
+    run_both(P, w, bits, n, synth.PER_TENSOR, f"per-tensor {shape}")
+
+
+def test_long_channels_split_into_tiles(P):
+    rng = np.random.default_rng(77)
+    w = rng.laplace(0, 0.02, size=(3, 30011)).astype(np.float32)
+    run_both(P, w, 4, 500, synth.PER_CHANNEL, "per-channel K=30011")
+
+
+# ------------------------------------------------------------------ degenerate
+def test_degenerate_groups(P):
+    w = np.zeros((8, 100), np.float32)
+    w[1, 40] = -0.5                                 # single non-zero
+    w[2, :] = 0.25
+    w[2, ::2] *= -1                                 # all magnitudes equal
+    w[3, :50] = 1.0
+    w[3, 50:] = -0.125                              # two magnitudes
+    w[4, :] = np.linspace(-1, 1, 100)               # uniform spread: optimum may sit above m/2
+    w[5, :] = np.float32(1e-20) * np.linspace(-1, 1, 100).astype(np.float32)
+    w[6, :] = np.float32(1e20) * np.linspace(-1, 1, 100).astype(np.float32)
+    w[7, :] = np.random.default_rng(1).standard_normal(100).astype(np.float32) ** 3
+    run_both(P, w, 4, 100, synth.PER_CHANNEL, "degenerate")
+    run_both(P, w[:5], 3, 64, synth.PER_TENSOR, "degenerate per-tensor")
+
+
+def test_non_finite_groups(P):
+    w = np.random.default_rng(2).standard_normal((6, 300)).astype(np.float32)
+    w[1, 7] = np.inf
+    w[3, 0] = np.nan
+    w[4, 299] = -np.inf
+    run_both(P, w, 4, 100, synth.PER_CHANNEL, "non-finite")
+    w2 = w[:2].copy()
+    run_both(P, w2, 4, 50, synth.PER_TENSOR, "non-finite per-tensor")
+
+
+def test_out_of_range_values_saturate(P):
+    import torch
+    w = np.array([[2.0, -3.0, 1.5, 0.1, -0.4]], np.float32)
+    p, m = np.array([0.375], np.float32), np.array([1.5], np.float32)
+    q = P.quantize(torch.from_numpy(w).cuda(), 3, torch.from_numpy(p).cuda(), torch.from_numpy(m).cuda())
+    q = tuple(t.cpu().numpy() for t in q)
+    assert_quantize_matches(q, R.quantize(w, 3, p, m), "saturation")
+    assert q[2][0, :3].tolist() == [1.5, -1.5, 1.5]
+
+
+def test_repeatable(P):
+    import torch
+    w = torch.from_numpy(synth.workload(2).tensor(30)).cuda()
+    a = to_np(P.search(w, 4, 1000))
+    b = to_np(P.search(w, 4, 1000))
+    for k in a:
+        np.testing.assert_array_equal(a[k], b[k])
+
+
+# ------------------------------------------------------------- model-level calls
+def _list_case(P, tensors, bits, n, mode, what, check_groups=None):
+    """Runs search_list + quantize_list on the GPU over all tensors and checks
+    the tensors / groups named in check_groups (default: everything)."""
+    import torch
+    say(f"[case] {what}: {len(tensors)} tensors bits={bits} n={n} mode={mode}")
+    dev = [torch.from_numpy(t).cuda() for t in tensors]
+    tl = P.TensorList(dev, mode)
+    out = P.search_list(tl, bits, n)
+    torch.cuda.synchronize()
+    say(f"  search done, shape {P.last_search_shape()}")
+    codes, flags, w_hat = P.quantize_list(tl, bits, out["p_star"], out["m"])
+    torch.cuda.synchronize()
+    say("  quantize done")
+    g = to_np(out)
+    todo = check_groups if check_groups is not None else {i: None for i in range(len(tensors))}
+    for ti, rows in todo.items():
+        w = tensors[ti]
+        go, eo = tl.group_offsets[ti], tl.elem_offsets[ti]
+        C, K = w.shape
+        if mode == synth.PER_TENSOR:
+            r = R.search(w, bits, n, mode, want_curve=True)
+            gs = {k: v[go:go + 1] for k, v in g.items()}
+            assert_search_matches(gs, r, f"{what} tensor {ti}")
+            sl = slice(eo, eo + C * K)
+            got = tuple(t[sl].cpu().numpy().reshape(C, K) for t in (codes, flags, w_hat))
+            want = R.quantize(w, bits, gs["p_star"], gs["m"], mode)
+            assert_quantize_matches(got, want, f"{what} tensor {ti}")
+        else:
+            rows = np.arange(C) if rows is None else np.asarray(rows)
+            r = R.search(w[rows], bits, n, mode, want_curve=True)
+            gs = {k: v[go + rows] for k, v in g.items()}
+            assert_search_matches(gs, r, f"{what} tensor {ti}")
+            got = tuple(t[eo:eo + C * K].view(C, K)[torch.from_numpy(rows).cuda()].cpu().numpy()
+                        for t in (codes, flags, w_hat))
+            want = R.quantize(w[rows], bits, gs["p_star"], gs["m"], mode)
+            assert_quantize_matches(got, want, f"{what} tensor {ti}")
+    return tl
+
+
+def test_list_small_mixed(P):
+    rng = np.random.default_rng(5)
+    shapes = [(7, 9), (16, 27), (5, 4608), (3, 9000), (40, 64), (1, 1), (12, 577)]
+    tensors = [rng.laplace(0, 0.04, size=s).astype(np.float32) for s in shapes]
+    _list_case(P, tensors, 4, 300, synth.PER_CHANNEL, "list mixed per-channel")
+    _list_case(P, tensors, 3, 200, synth.PER_TENSOR, "list mixed per-tensor")
+
+
+def _sample_rows(C, count, rng):
+    return np.sort(rng.choice(C, size=min(C, count), replace=False))
+
+
+def test_workload2_full_size_sampled(P):
+    wl = synth.workload(2)
+    tensors = list(wl.tensors())
+    rng = np.random.default_rng(2)
+    check = {t: _sample_rows(tensors[t].shape[0], 6, rng) for t in range(wl.n_tensors)}
+    _list_case(P, tensors, wl.bits, wl.n_cand, wl.mode, "workload2", check)
+
+
+def test_workload3_full_size_sampled(P):
+    wl = synth.workload(3)
+    tensors = list(wl.tensors())
+    rng = np.random.default_rng(3)
+    check = {t: _sample_rows(tensors[t].shape[0], 24, rng) for t in range(wl.n_tensors)}
+    _list_case(P, tensors, wl.bits, wl.n_cand, wl.mode, "workload3", check)
+
+
+def test_workload4_full_size_sampled(P):
+    wl = synth.workload(4)
+    tensors = list(wl.tensors())
+    sizes = np.array([t.size for t in tensors])
+    order = np.argsort(sizes)
+    picks = sorted({int(order[0]), int(order[1]), int(order[len(order) // 4]),
+                    int(order[len(order) // 2]), int(order[3 * len(order) // 4]), int(order[-1])})
+    _list_case(P, tensors, wl.bits, wl.n_cand, wl.mode, "workload4", {t: None for t in picks})
+
+
+def test_workload5_full_size_sampled(P):
+    wl = synth.workload(5)
+    tensors = list(wl.tensors())
+    rng = np.random.default_rng(5)
+    check = {t: _sample_rows(tensors[t].shape[0], 12, rng) for t in range(wl.n_tensors)}
+    _list_case(P, tensors, wl.bits, wl.n_cand, wl.mode, "workload5", check)
+
+
+# --------------------------------------------------------------------- ABI errors
+def test_error_statuses_write_nothing(P):
+    import torch
+    w = torch.ones((4, 16), device="cuda")
+    with pytest.raises(P.PwlqError) as e:
+        P.search(w, 9, 10)
+    assert e.value.status == 1
+    with pytest.raises(P.PwlqError) as e:
+        P.search(w, 4, 0)
+    assert e.value.status == 1
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(P.PwlqError) as e:
+        P.search(w, 4, 10, workspace=small)
+    assert e.value.status == 3
+    ps = torch.full((4,), 0.5, device="cuda")
+    with pytest.raises(P.PwlqError):
+        P.quantize(w, 1, ps, ps)
+    torch.cuda.synchronize()
