@@ -1,0 +1,183 @@
+#!/usr/bin/env python3
+"""Benchmark of the PWLQ hot path on one MI355X.
+
+A step is one pass of the whole path over the ResNet-50-shaped weight set
+(54 tensors, 27 560 channels, 25.5 M binary32 weights, already resident in
+HBM): pwlq_search_list (absmax, partition, candidate evaluation, refine,
+argmin) followed by pwlq_quantize_list (codes, flags, dequantized weights),
+per channel, b = 4, 1000 candidate breakpoints.
+
+Prints one JSON line.  `value` is candidate-element evaluations per second of
+the whole step; `roofline` describes the dominant kernel (the candidate
+evaluation kernel) against the chip's binary32 vector issue rate;
+`cpu_baseline` is the CPU oracle timed on this machine's host cores on a
+stated sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# Algorithmic work of one (element, candidate) evaluation in its plain
+# branch-free form: compare, three selects, subtract, multiply, round,
+# fused multiply-add (error), fused multiply-add (accumulate).
+LANE_OPS_PER_EVAL = 9
+# 157.3 TFLOP/s binary32 vector peak = 256 CUs x 128 lanes x 2 flop (FMA) x 2.4 GHz,
+# i.e. 78.6e12 lane-instructions per second (one VALU instruction on one lane)
+PEAK_LANE_OPS = 256 * 128 * 2.4e9
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=2, help="1..5 (default 2: ResNet-50 shapes)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path "
+              "(groups are independent; see DESIGN.md for how it would shard). "
+              "Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2002_00104_amd import pwlq, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    wl = synth.workload(args.workload)
+    host = list(wl.tensors())
+    dev = [torch.from_numpy(t).cuda() for t in host]
+    tl = pwlq.TensorList(dev, wl.mode)
+    ws_search = torch.empty(pwlq.search_list_workspace_bytes(tl, wl.bits, wl.n_cand),
+                            dtype=torch.uint8, device="cuda")
+    ws_quant = torch.empty(max(256, pwlq.quantize_list_workspace_bytes(tl, wl.bits)),
+                           dtype=torch.uint8, device="cuda")
+    out = pwlq.alloc_search_outputs(tl.n_groups, "cuda")
+    qout = pwlq.alloc_quantize_outputs(tl.n_elements, "cuda")
+
+    def step():
+        pwlq.search_list(tl, wl.bits, wl.n_cand, workspace=ws_search, out=out)
+        pwlq.quantize_list(tl, wl.bits, out["p_star"], out["m"], workspace=ws_quant, out=qout)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    pwlq.profile_enable(True)
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e2 = torch.cuda.Event(enable_timing=True)
+    k_search_ms, k_emit_ms, search_ms, quant_ms = [], [], [], []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        e0.record()
+        pwlq.search_list(tl, wl.bits, wl.n_cand, workspace=ws_search, out=out)
+        e1.record()
+        pwlq.quantize_list(tl, wl.bits, out["p_star"], out["m"], workspace=ws_quant, out=qout)
+        e2.record()
+        k_search_ms.append(pwlq.profile_last_ms(0))       # waits for the kernel's end event
+        k_emit_ms.append(pwlq.profile_last_ms(1))
+        e2.synchronize()
+        search_ms.append(e0.elapsed_time(e1))
+        quant_ms.append(e1.elapsed_time(e2))
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    pwlq.profile_enable(False)
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    evals = wl.n_evals
+    value = evals / (ms_per_step * 1e-3)
+    ks = float(np.mean(k_search_ms))
+    achieved = LANE_OPS_PER_EVAL * evals / (ks * 1e-3)
+    emit_ms = float(np.mean(k_emit_ms))
+    result = {
+        "metric": "breakpoint-search candidate-elem evals/s; ResNet-50-shape per-channel PWLQ ms",
+        "value": value,
+        "unit": "candidate-element evaluations/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": f"configs[{wl.index - 1}] {wl.name}: {wl.n_tensors} tensors, "
+                        f"{wl.n_groups} groups, {wl.n_elements} fp32 weights, "
+                        f"{'per-channel' if wl.mode == 0 else 'per-tensor'}, b={wl.bits}, "
+                        f"{wl.n_cand} candidates",
+            "evals_per_step": evals,
+            "search_ms": float(np.mean(search_ms)),
+            "quantize_ms": float(np.mean(quant_ms)),
+            "search_evals_per_s": evals / (float(np.mean(search_ms)) * 1e-3),
+        },
+        "roofline": {
+            "kernel": pwlq.kernel_name(0),
+            "bound": "alu",
+            "achieved": achieved / 1e12,
+            "peak": PEAK_LANE_OPS / 1e12,
+            "unit": "Tlane-op/s (fp32 VALU lane-instructions; 9 per evaluation, algorithmic)",
+            "frac": achieved / PEAK_LANE_OPS,
+            "traffic": None,
+            "kernel_ms": ks,
+            "kernel_evals_per_s": evals / (ks * 1e-3),
+        },
+        "quantize_roofline": {
+            "kernel": pwlq.kernel_name(1),
+            "bound": "hbm",
+            "achieved": 10.0 * wl.n_elements / (emit_ms * 1e-3) / 1e9,
+            "peak": 8000.0,
+            "unit": "GB/s",
+            "frac": 10.0 * wl.n_elements / (emit_ms * 1e-3) / 8e12,
+            "kernel_ms": emit_ms,
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import pwlq_ref
+        pwlq_ref.search(host[0][:2], wl.bits, 8, wl.mode)            # load the library
+        if wl.mode == synth.PER_CHANNEL:
+            stride = 2 if wl.n_evals > 4e9 else 1
+            if wl.index == 5:
+                stride = 16
+            sample = [t[::stride] for t in host]
+            what = f"every {stride}th channel of every tensor" if stride > 1 else "whole workload"
+        else:
+            order = np.argsort([t.size for t in host])
+            sample = [host[i] for i in order[: len(order) // 2]]
+            what = "the smaller half of the tensors"
+        c0 = time.perf_counter()
+        n_eval_cpu = 0
+        for t in sample:
+            t = np.ascontiguousarray(t)
+            pwlq_ref.search(t, wl.bits, wl.n_cand, wl.mode)
+            n_eval_cpu += t.size * wl.n_cand
+        c1 = time.perf_counter()
+        result["cpu_baseline"] = {
+            "value": n_eval_cpu / (c1 - c0),
+            "unit": "candidate-element evaluations/s",
+            "cores": pwlq_ref.num_threads(),
+            "kind": "oracle",
+            "sample": f"search only, {what} ({n_eval_cpu:.3e} evaluations, {c1 - c0:.1f} s)",
+        }
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
