@@ -246,7 +246,7 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
     double *part64 = (double *)(ws + pl.off_part);
 
     const int NT = (int)pl.n_tiles;
-    k_tile_absmax<<<NT, kWG, 0, stream>>>(tb, tile_max);
+    if (pl.n_mgroups > 0) k_tile_absmax<<<NT, kWG, 0, stream>>>(tb, tile_max);
     if (pl.nblk <= 32) {
         k_prep<true><<<NT, kWG, sizeof(int) * pl.nblk * kWG, stream>>>(
             tb, n_cand, pl.nblk, tile_max, gm, offsets, sorted);
@@ -262,9 +262,11 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
     k_search<<<(unsigned)wgs, kWG, 0, stream>>>(tb, n_cand, pl.nblk, bits, (int)units_padded, ny,
                                                 offsets, sorted, sse32);
     profile_mark(1, stream);
-    k_flag<<<(int)pl.n_groups, kWG, 0, stream>>>(tb, n_cand, pl.nwords, gm, sse32, mask);
-    k_exact<<<NT, kWG, 0, stream>>>(tb, n_cand, pl.nwords, bits, gm, mask, part64, p_star, m_out,
-                                    k_star, mse);
+    if (pl.n_mgroups > 0)
+        k_flag<<<(int)pl.n_mgroups, kWG, 0, stream>>>(tb, n_cand, pl.nwords, gm, sse32, mask);
+    const size_t lmask_bytes = sizeof(uint32_t) * 8 * (size_t)((n_cand + kWG - 1) / kWG);
+    k_exact<<<NT, kWG, lmask_bytes, stream>>>(tb, n_cand, pl.nwords, bits, gm, sse32, mask, part64,
+                                              p_star, m_out, k_star, mse);
     if (pl.n_mgroups > 0)
         k_final<<<(int)pl.n_mgroups, kWG, 0, stream>>>(tb, n_cand, pl.nwords, gm, mask, part64,
                                                        p_star, m_out, k_star, mse);

@@ -15,6 +15,7 @@ constexpr int kWG = 256;          // threads per workgroup (4 wavefronts of 64)
 constexpr int kWaves = kWG / 64;
 constexpr int kBlk = 64;          // candidates per wavefront: lane = candidate
 constexpr int kTileMax = 8192;    // longest run of a group handled by one workgroup
+constexpr int kPerThread = kTileMax / kWG;  // elements of a tile held by one thread
 constexpr int kUnitElems = 4096;  // small tiles are batched up to about this many elements
 constexpr int kVec = 8;           // elements per scalar vector load in the search loop
 constexpr int kChunk = 128;       // elements per inner fp32 accumulation chunk
@@ -43,14 +44,23 @@ struct TileInfo {
 };
 
 // largest i in [0, nt) with prefix[i] <= x; prefix[nt] > x is required
+// prefix is non-decreasing with prefix[0] = 0, and x is the same in every lane.
+// Every lane tests one entry and a ballot counts how many are <= x, so the
+// lookup costs one memory round trip per 64 tensors instead of one per halving
+// step.  Must be called with all 64 lanes of the wavefront active.
 __device__ inline int find_tensor(const int *__restrict__ prefix, int nt, int x)
 {
-    int lo = 0, hi = nt;
-    while (hi - lo > 1) {
-        int mid = (lo + hi) >> 1;
-        if (prefix[mid] <= x) lo = mid; else hi = mid;
+    if (nt == 1) return 0;
+    const int lane = threadIdx.x & 63;
+    int count = 0;
+    for (int base = 0; base < nt; base += 64) {
+        const int i = base + lane;
+        const bool le = (i < nt) && (prefix[i] <= x);
+        const unsigned long long bal = __ballot(le);
+        count += __builtin_popcountll(bal);
+        if (bal != ~0ull) break;
     }
-    return lo;
+    return __builtin_amdgcn_readfirstlane(count - 1);
 }
 
 __device__ inline TileInfo tile_info(const TensorRec &r, int tensor, int t)

@@ -73,6 +73,8 @@ __device__ inline TileInfo tile_of(const Tables &tb, int t, TensorRec &r)
 }
 
 // ------------------------------------------------------------------ absmax
+// Only groups cut into several tiles need this pass; a single-tile group finds
+// its absmax inside k_prep.
 __global__ __launch_bounds__(kWG) void k_tile_absmax(Tables tb, float *__restrict__ tile_max)
 {
     __shared__ float red[kWaves];
@@ -80,6 +82,7 @@ __global__ __launch_bounds__(kWG) void k_tile_absmax(Tables tb, float *__restric
     const int t = blockIdx.x;
     TensorRec r;
     TileInfo ti = tile_of(tb, t, r);
+    if (r.tpg == 1) return;
     float mx = 0.0f;
     int bad = 0;
     for (int i = threadIdx.x; i < ti.len; i += kWG) {
@@ -102,10 +105,10 @@ __global__ __launch_bounds__(kWG) void k_tile_absmax(Tables tb, float *__restric
 // breakpoint at u = k.  Bucket j holds the elements whose region differs among
 // the candidates 64j+1 .. 64j+64; every earlier bucket is centre for all of
 // them, every later bucket is tail for all of them.
-__device__ inline float to_units(float w, float m, float nf)
+__device__ inline float to_units(float a, float m, float nf)
 {
-    float u = (fabsf(w) / m) * nf;
-    return fminf(u, nf);
+    float u = (a / m) * nf;
+    return fminf(fmaxf(u, 0.0f), nf);     // also maps a NaN to 0
 }
 __device__ inline int bucket_of(float u)
 {
@@ -114,8 +117,24 @@ __device__ inline int bucket_of(float u)
     return (kc - 1) >> 6;
 }
 
-// sorted layout of one tile: [pad zeros][bucket 0][bucket 1]...; the padded
-// length is a multiple of kVec and off[j] is the start of bucket j.
+// inclusive prefix sum over the 64 lanes of a wavefront
+__device__ inline int wave_scan_incl(int v)
+{
+    const int lane = threadIdx.x & 63;
+    for (int off = 1; off < 64; off <<= 1) {
+        int o = __shfl_up(v, off, 64);
+        if (lane >= off) v += o;
+    }
+    return v;
+}
+
+// Sorted layout of one tile: [pad zeros][bucket 0][bucket 1]...[one vector of
+// slack]; the padded length is a multiple of kVec and off[j] is the start of
+// bucket j.  The tile's elements stay in registers between the passes, so the
+// weights are read from memory once.  kPrivate (at most 32 buckets): every
+// thread counts into its own histogram column and positions are assigned in
+// (bucket, thread, element) order, so the layout is repeatable; otherwise LDS
+// integer atomics assign positions inside a bucket in arrival order.
 template <bool kPrivate>
 __global__ __launch_bounds__(kWG) void k_prep(Tables tb, int n, int nblk,
                                                const float *__restrict__ tile_max,
@@ -126,24 +145,41 @@ __global__ __launch_bounds__(kWG) void k_prep(Tables tb, int n, int nblk,
     extern __shared__ int hist[];     // kPrivate: [nblk][kWG], else [nblk]
     __shared__ float redm[kWaves];
     __shared__ int redbad[kWaves];
-    __shared__ int scan[kWG];
+    __shared__ int wtot[32 * kWaves];
+    __shared__ int scan_lds[kWaves];
     const int t = blockIdx.x;
     const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
     TensorRec r;
     TileInfo ti = tile_of(tb, t, r);
+    const int len = ti.len;
 
-    // group absmax from the per-tile maxima
-    const int tile0 = r.tile_base + ti.group_local * r.tpg;
+    float a[kPerThread];
+#pragma unroll
+    for (int e = 0; e < kPerThread; ++e) {
+        const int i = tid + e * kWG;
+        a[e] = (i < len) ? fabsf(ti.src[i]) : 0.0f;
+    }
+
+    // group absmax: from the registers (single-tile group) or the tile maxima
     float m = 0.0f;
     int bad = 0;
-    for (int j = tid; j < r.tpg; j += kWG) {
-        float v = tile_max[tile0 + j];
-        bad |= (v != v);
-        m = fmaxf(m, v);
+    if (r.tpg == 1) {
+#pragma unroll
+        for (int e = 0; e < kPerThread; ++e) { bad |= (a[e] != a[e]); m = fmaxf(m, a[e]); }
+    } else {
+        const int tile0 = r.tile_base + ti.group_local * r.tpg;
+        for (int j = tid; j < r.tpg; j += kWG) {
+            float v = tile_max[tile0 + j];
+            bad |= (v != v);
+            m = fmaxf(m, v);
+        }
     }
     m = wave_max(m);
     bad = wave_or(bad);
-    if ((tid & 63) == 0) { redm[tid >> 6] = m; redbad[tid >> 6] = bad; }
+    if (lane == 0) { redm[wave] = m; redbad[wave] = bad; }
+    if (!kPrivate) for (int i = tid; i < nblk; i += kWG) hist[i] = 0;
     __syncthreads();
     m = redm[0];
     bad = redbad[0];
@@ -153,46 +189,66 @@ __global__ __launch_bounds__(kWG) void k_prep(Tables tb, int n, int nblk,
 
     const bool usable = (m > 0.0f) && (m < __builtin_inff());
     const float nf = (float)n;
-    const int len = ti.len;
     const int padded = (len + kVec - 1) / kVec * kVec;
     const int pad = padded - len;
     float *out = sorted + ti.sorted_off;
     int *off = offsets + (long long)t * (nblk + 1);
 
-    const int nhist = kPrivate ? nblk * kWG : nblk;
-    for (int i = tid; i < nhist; i += kWG) hist[i] = 0;
-    __syncthreads();
-
-    // pass A: histogram
-    for (int i = tid; i < len; i += kWG) {
-        float u = usable ? to_units(ti.src[i], m, nf) : 0.0f;
-        int b = bucket_of(u);
-        if (kPrivate) hist[b * kWG + tid] += 1;
-        else atomicAdd(&hist[b], 1);
+    // pass A: units and histogram
+    if (kPrivate) for (int b = 0; b < nblk; ++b) hist[b * kWG + tid] = 0;
+#pragma unroll
+    for (int e = 0; e < kPerThread; ++e) {
+        const int i = tid + e * kWG;
+        if (i < len) {
+            const float u = usable ? to_units(a[e], m, nf) : 0.0f;
+            a[e] = u;
+            const int b = bucket_of(u);
+            if (kPrivate) hist[b * kWG + tid] += 1;
+            else atomicAdd(&hist[b], 1);
+        }
     }
-    __syncthreads();
 
-    // exclusive scan of the histogram in (bucket, thread) order
-    {
-        const int per = kPrivate ? nblk : (nblk + kWG - 1) / kWG;
-        const int lo = tid * per;
-        int hi = lo + per;
-        if (hi > nhist) hi = nhist;
-        int sum = 0;
-        for (int i = lo; i < hi; ++i) sum += hist[i];
-        scan[tid] = sum;
-        __syncthreads();
-        if (tid == 0) {
-            int run = 0;
-            for (int i = 0; i < kWG; ++i) { int v = scan[i]; scan[i] = run; run += v; }
+    // exclusive positions
+    if (kPrivate) {
+        for (int b = 0; b < nblk; ++b) {
+            const int c = hist[b * kWG + tid];
+            const int incl = wave_scan_incl(c);
+            hist[b * kWG + tid] = incl - c;                 // exclusive inside the wavefront
+            if (lane == 63) wtot[b * kWaves + wave] = incl;
         }
         __syncthreads();
-        int run = scan[tid];
-        for (int i = lo; i < hi; ++i) { int v = hist[i]; hist[i] = run; run += v; }
+        if (wave == 0) {
+            int w[kWaves];
+            int tot = 0;
+#pragma unroll
+            for (int i = 0; i < kWaves; ++i) {
+                w[i] = (lane < nblk) ? wtot[lane * kWaves + i] : 0;
+                tot += w[i];
+            }
+            int run = wave_scan_incl(tot) - tot;            // first position of bucket `lane`
+            if (lane < nblk) {
+                off[lane] = pad + run;
+#pragma unroll
+                for (int i = 0; i < kWaves; ++i) { wtot[lane * kWaves + i] = run; run += w[i]; }
+            }
+            if (lane == 0) off[nblk] = pad + len;
+        }
+    } else {
+        __syncthreads();
+        const int per = (nblk + kWG - 1) / kWG;
+        const int lo = tid * per;
+        int hi = lo + per;
+        if (hi > nblk) hi = nblk;
+        int sum = 0;
+        for (int i = lo; i < hi; ++i) sum += hist[i];
+        const int incl = wave_scan_incl(sum);
+        if (lane == 63) scan_lds[wave] = incl;
+        __syncthreads();
+        int run = incl - sum;
+        for (int i = 0; i < wave; ++i) run += scan_lds[i];
+        for (int i = lo; i < hi; ++i) { int v = hist[i]; hist[i] = run; off[i] = pad + run; run += v; }
+        if (tid == 0) off[nblk] = pad + len;
     }
-    __syncthreads();
-    for (int b = tid; b <= nblk; b += kWG)
-        off[b] = pad + (b < nblk ? hist[kPrivate ? b * kWG : b] : len);
     for (int i = tid; i < pad + kVec; i += kWG) {
         if (i < pad) out[i] = 0.0f;
         else out[padded + (i - pad)] = 0.0f;      // one vector of slack for the prefetch
@@ -200,13 +256,21 @@ __global__ __launch_bounds__(kWG) void k_prep(Tables tb, int n, int nblk,
     __syncthreads();
 
     // pass B: scatter
-    for (int i = tid; i < len; i += kWG) {
-        float u = usable ? to_units(ti.src[i], m, nf) : 0.0f;
-        int b = bucket_of(u);
-        int pos;
-        if (kPrivate) { pos = hist[b * kWG + tid]; hist[b * kWG + tid] = pos + 1; }
-        else pos = atomicAdd(&hist[b], 1);
-        out[pad + pos] = u;
+#pragma unroll
+    for (int e = 0; e < kPerThread; ++e) {
+        const int i = tid + e * kWG;
+        if (i < len) {
+            const float u = a[e];
+            const int b = bucket_of(u);
+            int pos;
+            if (kPrivate) {
+                pos = wtot[b * kWaves + wave] + hist[b * kWG + tid];
+                hist[b * kWG + tid] += 1;
+            } else {
+                pos = atomicAdd(&hist[b], 1);
+            }
+            out[pad + pos] = u;
+        }
     }
 }
 
@@ -329,10 +393,16 @@ __global__ __launch_bounds__(kWG) void k_search(Tables tb, int n, int nblk, int 
 }
 
 // -------------------------------------------------------------------- flag
-// Binary32 SSE (candidate units) summed over the group's tiles in binary64;
-// every candidate within the rounding slack of the minimum is kept.  The slack
-// bounds twice the error of k_search: eps = 2^-21 n per element error (units),
-// plus 3e-5 relative for the binary32 accumulation.
+// The binary32 SSE of k_search (candidate units) is only a filter: every
+// candidate within the rounding slack of the minimum is kept and re-evaluated
+// exactly.  The slack bounds twice the error of k_search: eps = 2^-21 n per
+// element error (candidate units) and 3e-5 relative for the binary32 sums.
+__device__ inline double keep_threshold(double mn, double count, int n)
+{
+    const double eps = (double)n * 4.76837158203125e-07;   // 2^-21 n
+    return mn + 2.0 * (3e-5 * mn + 2.0 * eps * sqrt(count * mn) + count * eps * eps);
+}
+
 __device__ inline double group_sse(const float *__restrict__ sse32, long long tile0, int tpg,
                                    int n, int k0)
 {
@@ -341,17 +411,21 @@ __device__ inline double group_sse(const float *__restrict__ sse32, long long ti
     return v;
 }
 
+// Groups spread over several tiles: tile sums added in binary64, kept
+// candidates written as a bit mask (bit k-1 of the group's row).
 __global__ __launch_bounds__(kWG) void k_flag(Tables tb, int n, int nwords,
                                               const float *__restrict__ gm,
                                               const float *__restrict__ sse32,
                                               uint32_t *__restrict__ mask)
 {
     __shared__ double lds[kWaves];
-    const int g = blockIdx.x;
+    const int mg = blockIdx.x;
     const int tid = threadIdx.x;
-    const int tensor = find_tensor(tb.group_prefix, tb.nt, g);
+    const int tensor = find_tensor(tb.mgroup_prefix, tb.nt, mg);
     const TensorRec r = rec_of(tb, tensor);
-    const long long tile0 = r.tile_base + (long long)(g - r.group_base) * r.tpg;
+    const int gl = mg - r.mgroup_base;
+    const int g = r.group_base + gl;
+    const long long tile0 = r.tile_base + (long long)gl * r.tpg;
     uint32_t *gmask = mask + (long long)g * nwords;
     const float m = gm[g];
     if (!(m > 0.0f) || !(m < __builtin_inff())) {
@@ -364,9 +438,7 @@ __global__ __launch_bounds__(kWG) void k_flag(Tables tb, int n, int nwords,
     double mn = __builtin_inf();
     for (int k0 = tid; k0 < n; k0 += kWG) mn = fmin(mn, group_sse(sse32, tile0, r.tpg, n, k0));
     mn = block_min(mn, lds);
-    const double eps = (double)n * 4.76837158203125e-07;   // 2^-21 n
-    const double cnt = (double)r.gcount;
-    const double thr = mn + 2.0 * (3e-5 * mn + 2.0 * eps * sqrt(cnt * mn) + cnt * eps * eps);
+    const double thr = keep_threshold(mn, (double)r.gcount, n);
     for (int wi = tid; wi < nwords; wi += kWG) {
         uint32_t word = 0;
         for (int b = 0; b < 32; ++b) {
@@ -378,27 +450,116 @@ __global__ __launch_bounds__(kWG) void k_flag(Tables tb, int n, int nwords,
 }
 
 // ------------------------------------------------------------------- exact
-// Canonical evaluation of one candidate over one tile: binary32 code (Eq.3),
-// binary64 error  s*code + z - |w|, summed per thread in index order and then
-// over the workgroup in a fixed tree.
-__device__ inline double tile_sse_exact(const float *__restrict__ src, int len, const Pieces &q,
-                                        double *lds)
+// Canonical evaluation of the kept candidates over one tile: binary32 code
+// (Eq.3), binary64 error  s*code + z - |w|, summed per thread in index order and
+// then over the workgroup in a fixed tree.  The tile's magnitudes stay in
+// registers and up to kBatch candidates share one pass.  A single-tile group
+// does its own filtering (mask in LDS) and its own argmin.
+struct BitCursor {
+    const uint32_t *words;
+    int nwords, wi;
+    uint32_t word;
+};
+__device__ inline int next_candidate(BitCursor &c)
 {
-    double acc = 0.0;
-    for (int i = threadIdx.x; i < len; i += kWG) {
-        const float a = fabsf(src[i]);
-        bool tail;
-        const float code = piece_code(q, a, tail);
-        const double s = tail ? (double)q.s2 : (double)q.s1;
-        const double z = tail ? (double)q.p : 0.0;
-        const double e = (double)code * s + z - (double)a;
-        acc += e * e;
+    while (c.word == 0) {
+        if (++c.wi >= c.nwords) return -1;
+        c.word = c.words[c.wi];
     }
-    return block_sum(acc, lds);
+    const int b = __builtin_ctz(c.word);
+    c.word &= c.word - 1;
+    return c.wi * 32 + b + 1;
+}
+
+__device__ inline double exact_error_sq(const Pieces &q, float a)
+{
+    bool tail;
+    const float code = piece_code(q, a, tail);
+    const double s = tail ? (double)q.s2 : (double)q.s1;
+    const double z = tail ? (double)q.p : 0.0;
+    const double e = (double)code * s + z - (double)a;
+    return e * e;
+}
+
+struct ExactState {
+    double best;
+    int best_k;
+    int slot;
+};
+
+// Evaluates every kept candidate over a tile whose threads hold kEpt elements
+// each.  Candidates are taken one or two at a time (there are rarely more).
+template <int kEpt>
+__device__ inline void exact_tile(const float *__restrict__ src, int len, float m, int n, int bits,
+                                  BitCursor &cur, bool single, double *__restrict__ part,
+                                  double *lds, ExactState &st)
+{
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    // kEpt > 0: the thread's elements stay in registers; kEpt == 0 (long
+    // tiles): they are re-read for every pass (they sit in L2)
+    float a[kEpt > 0 ? kEpt : 1];
+    if (kEpt > 0) {
+#pragma unroll
+        for (int e = 0; e < kEpt; ++e) {
+            const int i = tid + e * kWG;
+            a[e] = (i < len) ? fabsf(src[i]) : 0.0f;
+        }
+    }
+    for (;;) {
+        const int k0 = next_candidate(cur);
+        if (k0 < 0) break;
+        const int k1 = next_candidate(cur);
+        const Pieces q0 = make_pieces(m, grid_point(m, k0, n), bits);
+        double acc0 = 0.0, acc1 = 0.0;
+        if (k1 < 0) {
+            if (kEpt > 0) {
+#pragma unroll
+                for (int e = 0; e < kEpt; ++e)
+                    if (tid + e * kWG < len) acc0 += exact_error_sq(q0, a[e]);
+            } else {
+                for (int i = tid; i < len; i += kWG) acc0 += exact_error_sq(q0, fabsf(src[i]));
+            }
+        } else {
+            const Pieces q1 = make_pieces(m, grid_point(m, k1, n), bits);
+            if (kEpt > 0) {
+#pragma unroll
+                for (int e = 0; e < kEpt; ++e) {
+                    if (tid + e * kWG < len) {
+                        acc0 += exact_error_sq(q0, a[e]);
+                        acc1 += exact_error_sq(q1, a[e]);
+                    }
+                }
+            } else {
+                for (int i = tid; i < len; i += kWG) {
+                    const float av = fabsf(src[i]);
+                    acc0 += exact_error_sq(q0, av);
+                    acc1 += exact_error_sq(q1, av);
+                }
+            }
+        }
+        acc0 = wave_sum(acc0);
+        acc1 = wave_sum(acc1);
+        __syncthreads();
+        if (lane == 0) { lds[wave * 2] = acc0; lds[wave * 2 + 1] = acc1; }
+        __syncthreads();
+        double s0 = lds[0], s1 = lds[1];
+        for (int w = 1; w < kWaves; ++w) { s0 += lds[w * 2]; s1 += lds[w * 2 + 1]; }
+        if (single) {
+            if (st.best_k < 0 || s0 < st.best) { st.best = s0; st.best_k = k0; }
+            if (k1 >= 0 && s1 < st.best) { st.best = s1; st.best_k = k1; }
+        } else if (tid == 0) {
+            part[st.slot] = s0;
+            if (k1 >= 0) part[st.slot + 1] = s1;
+        }
+        st.slot += (k1 >= 0) ? 2 : 1;
+    }
 }
 
 __global__ __launch_bounds__(kWG) void k_exact(Tables tb, int n, int nwords, int bits,
                                                const float *__restrict__ gm,
+                                               const float *__restrict__ sse32,
                                                const uint32_t *__restrict__ mask,
                                                double *__restrict__ part64,
                                                float *__restrict__ p_star,
@@ -406,45 +567,75 @@ __global__ __launch_bounds__(kWG) void k_exact(Tables tb, int n, int nwords, int
                                                int32_t *__restrict__ k_star,
                                                double *__restrict__ mse)
 {
-    __shared__ double lds[kWaves];
+    extern __shared__ uint32_t lmask[];          // single-tile groups: ceil(n/256)*8 words
+    __shared__ double lds[kWaves * 2];
     const int t = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
     TensorRec r;
     TileInfo ti = tile_of(tb, t, r);
     const bool single = r.tpg == 1;
     const float m = gm[ti.group];
     const long long og = r.out_group + ti.group_local;
-    const uint32_t *gmask = mask + (long long)ti.group * nwords;
+    const bool usable = (m > 0.0f) && (m < __builtin_inff());
+
+    BitCursor cur;
+    cur.wi = -1;
+    cur.word = 0;
+    if (single) {
+        const int lwords = (n + kWG - 1) / kWG * 8;
+        if (!usable) {
+            for (int wi = tid; wi < lwords; wi += kWG) lmask[wi] = (wi == 0 && m == 0.0f) ? 1u : 0u;
+        } else {
+            const float *row = sse32 + (long long)t * n;
+            double mn = __builtin_inf();
+            for (int k0 = tid; k0 < n; k0 += kWG) mn = fmin(mn, (double)row[k0]);
+            mn = block_min(mn, lds);
+            const double thr = keep_threshold(mn, (double)r.gcount, n);
+            for (int base = 0; base < n; base += kWG) {
+                const int k0 = base + tid;
+                const bool keep = (k0 < n) && ((double)row[k0] <= thr);
+                const unsigned long long bal = __ballot(keep);
+                if (lane == 0) {
+                    lmask[(base >> 5) + wave * 2] = (uint32_t)bal;
+                    lmask[(base >> 5) + wave * 2 + 1] = (uint32_t)(bal >> 32);
+                }
+            }
+        }
+        __syncthreads();
+        cur.words = lmask;
+        cur.nwords = lwords;
+    } else {
+        cur.words = mask + (long long)ti.group * nwords;
+        cur.nwords = nwords;
+    }
+
     double *part = single ? nullptr
                           : part64 + (long long)(r.part_base + ti.local_tile) * n;
-    double best = 0.0;
-    int best_k = -1;
-    int slot = 0;
-    for (int wi = 0; wi < nwords; ++wi) {
-        uint32_t word = gmask[wi];
-        while (word) {
-            const int b = __builtin_ctz(word);
-            word &= word - 1;
-            const int k = wi * 32 + b + 1;
-            const Pieces q = make_pieces(m, grid_point(m, k, n), bits);
-            const double sse = tile_sse_exact(ti.src, ti.len, q, lds);
-            if (single) {
-                if (best_k < 0 || sse < best) { best = sse; best_k = k; }
-            } else if (threadIdx.x == 0) {
-                part[slot] = sse;
-            }
-            ++slot;
-        }
-    }
-    if (single && threadIdx.x == 0) {
+    ExactState st;
+    st.best = 0.0;
+    st.best_k = -1;
+    st.slot = 0;
+    if (ti.len <= kWG)
+        exact_tile<1>(ti.src, ti.len, m, n, bits, cur, single, part, lds, st);
+    else if (ti.len <= 4 * kWG)
+        exact_tile<4>(ti.src, ti.len, m, n, bits, cur, single, part, lds, st);
+    else if (ti.len <= 10 * kWG)
+        exact_tile<10>(ti.src, ti.len, m, n, bits, cur, single, part, lds, st);
+    else
+        exact_tile<0>(ti.src, ti.len, m, n, bits, cur, single, part, lds, st);
+
+    if (single && tid == 0) {
         m_out[og] = m;
-        if (best_k < 0) {
+        if (st.best_k < 0) {
             k_star[og] = -1;
             p_star[og] = __builtin_nanf("");
             mse[og] = __builtin_nan("");
         } else {
-            k_star[og] = best_k;
-            p_star[og] = grid_point(m, best_k, n);
-            mse[og] = best / (double)r.gcount;
+            k_star[og] = st.best_k;
+            p_star[og] = grid_point(m, st.best_k, n);
+            mse[og] = st.best / (double)r.gcount;
         }
     }
 }
