@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpwlq.so")
 SOURCES = [os.path.join(CSRC, "pwlq_api.hip")]
-HEADERS = [os.path.join(CSRC, "pwlq_device.h"), os.path.join(CSRC, "pwlq_kernels.h"),
+HEADERS = [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC)) if f.endswith(".h")] + [
            os.path.join(os.path.dirname(HERE), "include", "pwlq.h")]
 
 # -ffp-contract=off: the canonical code arithmetic must not be fused; fused

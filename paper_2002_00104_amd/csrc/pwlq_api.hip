@@ -87,7 +87,7 @@ int build_plan(Plan &pl, const pwlq_tensor_desc *desc, int n_tensors, int n_cand
         r.tpg = (int)tpg;
         r.ngroups = (int)groups;
         r.ntiles = (int)(groups * tpg);
-        r.stride = (r.tile_len + kVec - 1) / kVec * kVec + kVec;
+        r.stride = (r.tile_len + kVec - 1) / kVec * kVec + kVec;   // one spare vector: loads may run one ahead
         r.tpu = std::max(1, kUnitElems / r.tile_len);
         tmp[i] = r;
         order[i] = {i, r.tile_len};
@@ -254,12 +254,12 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
         k_prep<false><<<NT, kWG, sizeof(int) * pl.nblk, stream>>>(
             tb, n_cand, pl.nblk, tile_max, gm, offsets, sorted);
     }
-    const int ny = (pl.nblk + kWaves - 1) / kWaves;
+    const int ny = (pl.nblk + kSearchWaves - 1) / kSearchWaves;
     const long long units_padded = (pl.n_units + 7) / 8 * 8;
     const long long wgs = units_padded * ny;
     if (wgs > 0x7fffffffLL) return fail(PWLQ_EINVAL, "search grid too large");
     profile_mark(0, stream);
-    k_search<<<(unsigned)wgs, kWG, 0, stream>>>(tb, n_cand, pl.nblk, bits, (int)units_padded, ny,
+    k_search<<<(unsigned)wgs, kSearchWaves * 64, 0, stream>>>(tb, n_cand, pl.nblk, bits, ny,
                                                 offsets, sorted, sse32);
     profile_mark(1, stream);
     if (pl.n_mgroups > 0)

@@ -14,6 +14,7 @@ namespace pwlq {
 constexpr int kWG = 256;          // threads per workgroup (4 wavefronts of 64)
 constexpr int kWaves = kWG / 64;
 constexpr int kBlk = 64;          // candidates per wavefront: lane = candidate
+constexpr int kSearchWaves = 16;  // wavefronts (candidate blocks) per search workgroup
 constexpr int kTileMax = 8192;    // longest run of a group handled by one workgroup
 constexpr int kPerThread = kTileMax / kWG;  // elements of a tile held by one thread
 constexpr int kUnitElems = 4096;  // small tiles are batched up to about this many elements

@@ -1,0 +1,206 @@
+// k_tile_absmax and k_prep: group absmax, rescaling to candidate units, partition by candidate block.
+#pragma once
+
+#include "pwlq_tables.h"
+
+namespace pwlq {
+
+// ------------------------------------------------------------------ absmax
+// Only groups cut into several tiles need this pass; a single-tile group finds
+// its absmax inside k_prep.
+__global__ __launch_bounds__(kWG) void k_tile_absmax(Tables tb, float *__restrict__ tile_max)
+{
+    __shared__ float red[kWaves];
+    __shared__ int redbad[kWaves];
+    const int t = blockIdx.x;
+    TensorRec r;
+    TileInfo ti = tile_of(tb, t, r);
+    if (r.tpg == 1) return;
+    float mx = 0.0f;
+    int bad = 0;
+    for (int i = threadIdx.x; i < ti.len; i += kWG) {
+        float a = fabsf(ti.src[i]);
+        bad |= (a != a);
+        mx = fmaxf(mx, a);
+    }
+    mx = wave_max(mx);
+    bad = wave_or(bad);
+    if ((threadIdx.x & 63) == 0) { red[threadIdx.x >> 6] = mx; redbad[threadIdx.x >> 6] = bad; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int i = 1; i < kWaves; ++i) { mx = fmaxf(mx, red[i]); bad |= redbad[i]; }
+        tile_max[t] = bad ? __builtin_nanf("") : mx;
+    }
+}
+
+// -------------------------------------------------------------------- prep
+// Magnitude in candidate units: u = |w|/m * n in [0, n]; candidate k has its
+// breakpoint at u = k.  Bucket j holds the elements whose region differs among
+// the candidates 64j+1 .. 64j+64; every earlier bucket is centre for all of
+// them, every later bucket is tail for all of them.
+__device__ inline float to_units(float a, float m, float nf)
+{
+    float u = (a / m) * nf;
+    return fminf(fmaxf(u, 0.0f), nf);     // also maps a NaN to 0
+}
+__device__ inline int bucket_of(float u)
+{
+    int kc = (int)ceilf(u);          // smallest candidate with u <= k
+    kc = kc < 1 ? 1 : kc;
+    return (kc - 1) >> 6;
+}
+
+// inclusive prefix sum over the 64 lanes of a wavefront
+__device__ inline int wave_scan_incl(int v)
+{
+    const int lane = threadIdx.x & 63;
+    for (int off = 1; off < 64; off <<= 1) {
+        int o = __shfl_up(v, off, 64);
+        if (lane >= off) v += o;
+    }
+    return v;
+}
+
+// Sorted layout of one tile: [pad zeros][bucket 0][bucket 1]...; the padded
+// length is a multiple of kVec and off[j] is the start of bucket j.  The tile's elements stay in registers between the passes, so the
+// weights are read from memory once.  kPrivate (at most 32 buckets): every
+// thread counts into its own histogram column and positions are assigned in
+// (bucket, thread, element) order, so the layout is repeatable; otherwise LDS
+// integer atomics assign positions inside a bucket in arrival order.
+template <bool kPrivate>
+__global__ __launch_bounds__(kWG) void k_prep(Tables tb, int n, int nblk,
+                                               const float *__restrict__ tile_max,
+                                               float *__restrict__ gm,
+                                               int *__restrict__ offsets,
+                                               float *__restrict__ sorted)
+{
+    extern __shared__ int hist[];     // kPrivate: [nblk][kWG], else [nblk]
+    __shared__ float redm[kWaves];
+    __shared__ int redbad[kWaves];
+    __shared__ int wtot[32 * kWaves];
+    __shared__ int scan_lds[kWaves];
+    const int t = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    TensorRec r;
+    TileInfo ti = tile_of(tb, t, r);
+    const int len = ti.len;
+
+    float a[kPerThread];
+#pragma unroll
+    for (int e = 0; e < kPerThread; ++e) {
+        const int i = tid + e * kWG;
+        a[e] = (i < len) ? fabsf(ti.src[i]) : 0.0f;
+    }
+
+    // group absmax: from the registers (single-tile group) or the tile maxima
+    float m = 0.0f;
+    int bad = 0;
+    if (r.tpg == 1) {
+#pragma unroll
+        for (int e = 0; e < kPerThread; ++e) { bad |= (a[e] != a[e]); m = fmaxf(m, a[e]); }
+    } else {
+        const int tile0 = r.tile_base + ti.group_local * r.tpg;
+        for (int j = tid; j < r.tpg; j += kWG) {
+            float v = tile_max[tile0 + j];
+            bad |= (v != v);
+            m = fmaxf(m, v);
+        }
+    }
+    m = wave_max(m);
+    bad = wave_or(bad);
+    if (lane == 0) { redm[wave] = m; redbad[wave] = bad; }
+    if (!kPrivate) for (int i = tid; i < nblk; i += kWG) hist[i] = 0;
+    __syncthreads();
+    m = redm[0];
+    bad = redbad[0];
+    for (int i = 1; i < kWaves; ++i) { m = fmaxf(m, redm[i]); bad |= redbad[i]; }
+    if (bad) m = __builtin_nanf("");
+    if (ti.tile_in_group == 0 && tid == 0) gm[ti.group] = m;
+
+    const bool usable = (m > 0.0f) && (m < __builtin_inff());
+    const float nf = (float)n;
+    const int padded = (len + kVec - 1) / kVec * kVec;
+    const int pad = padded - len;
+    float *out = sorted + ti.sorted_off;
+    int *off = offsets + (long long)t * (nblk + 1);
+
+    // pass A: units and histogram
+    if (kPrivate) for (int b = 0; b < nblk; ++b) hist[b * kWG + tid] = 0;
+#pragma unroll
+    for (int e = 0; e < kPerThread; ++e) {
+        const int i = tid + e * kWG;
+        if (i < len) {
+            const float u = usable ? to_units(a[e], m, nf) : 0.0f;
+            a[e] = u;
+            const int b = bucket_of(u);
+            if (kPrivate) hist[b * kWG + tid] += 1;
+            else atomicAdd(&hist[b], 1);
+        }
+    }
+
+    // exclusive positions
+    if (kPrivate) {
+        for (int b = 0; b < nblk; ++b) {
+            const int c = hist[b * kWG + tid];
+            const int incl = wave_scan_incl(c);
+            hist[b * kWG + tid] = incl - c;                 // exclusive inside the wavefront
+            if (lane == 63) wtot[b * kWaves + wave] = incl;
+        }
+        __syncthreads();
+        if (wave == 0) {
+            int w[kWaves];
+            int tot = 0;
+#pragma unroll
+            for (int i = 0; i < kWaves; ++i) {
+                w[i] = (lane < nblk) ? wtot[lane * kWaves + i] : 0;
+                tot += w[i];
+            }
+            int run = wave_scan_incl(tot) - tot;            // first position of bucket `lane`
+            if (lane < nblk) {
+                off[lane] = pad + run;
+#pragma unroll
+                for (int i = 0; i < kWaves; ++i) { wtot[lane * kWaves + i] = run; run += w[i]; }
+            }
+            if (lane == 0) off[nblk] = pad + len;
+        }
+    } else {
+        __syncthreads();
+        const int per = (nblk + kWG - 1) / kWG;
+        const int lo = tid * per;
+        int hi = lo + per;
+        if (hi > nblk) hi = nblk;
+        int sum = 0;
+        for (int i = lo; i < hi; ++i) sum += hist[i];
+        const int incl = wave_scan_incl(sum);
+        if (lane == 63) scan_lds[wave] = incl;
+        __syncthreads();
+        int run = incl - sum;
+        for (int i = 0; i < wave; ++i) run += scan_lds[i];
+        for (int i = lo; i < hi; ++i) { int v = hist[i]; hist[i] = run; off[i] = pad + run; run += v; }
+        if (tid == 0) off[nblk] = pad + len;
+    }
+    for (int i = tid; i < pad; i += kWG) out[i] = 0.0f;
+    __syncthreads();
+
+    // pass B: scatter
+#pragma unroll
+    for (int e = 0; e < kPerThread; ++e) {
+        const int i = tid + e * kWG;
+        if (i < len) {
+            const float u = a[e];
+            const int b = bucket_of(u);
+            int pos;
+            if (kPrivate) {
+                pos = wtot[b * kWaves + wave] + hist[b * kWG + tid];
+                hist[b * kWG + tid] += 1;
+            } else {
+                pos = atomicAdd(&hist[b], 1);
+            }
+            out[pad + pos] = u;
+        }
+    }
+}
+
+} // namespace pwlq

@@ -1,0 +1,325 @@
+// k_flag, k_exact, k_final: filter by the binary32 SSE, exact binary64 re-evaluation, argmin.
+#pragma once
+
+#include "pwlq_tables.h"
+
+namespace pwlq {
+
+// -------------------------------------------------------------------- flag
+// The binary32 SSE of k_search (candidate units) is only a filter: every
+// candidate within the rounding slack of the minimum is kept and re-evaluated
+// exactly.  The slack bounds twice the error of k_search: eps = 2^-21 n per
+// element error (candidate units) and 3e-5 relative for the binary32 sums.
+__device__ inline double keep_threshold(double mn, double count, int n)
+{
+    const double eps = (double)n * 4.76837158203125e-07;   // 2^-21 n
+    return mn + 2.0 * (3e-5 * mn + 2.0 * eps * sqrt(count * mn) + count * eps * eps);
+}
+
+__device__ inline double group_sse(const float *__restrict__ sse32, long long tile0, int tpg,
+                                   int n, int k0)
+{
+    double v = 0.0;
+    for (int j = 0; j < tpg; ++j) v += (double)sse32[(tile0 + j) * n + k0];
+    return v;
+}
+
+// Groups spread over several tiles: tile sums added in binary64, kept
+// candidates written as a bit mask (bit k-1 of the group's row).
+__global__ __launch_bounds__(kWG) void k_flag(Tables tb, int n, int nwords,
+                                              const float *__restrict__ gm,
+                                              const float *__restrict__ sse32,
+                                              uint32_t *__restrict__ mask)
+{
+    __shared__ double lds[kWaves];
+    const int mg = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int tensor = find_tensor(tb.mgroup_prefix, tb.nt, mg);
+    const TensorRec r = rec_of(tb, tensor);
+    const int gl = mg - r.mgroup_base;
+    const int g = r.group_base + gl;
+    const long long tile0 = r.tile_base + (long long)gl * r.tpg;
+    uint32_t *gmask = mask + (long long)g * nwords;
+    const float m = gm[g];
+    if (!(m > 0.0f) || !(m < __builtin_inff())) {
+        // all-zero group: every candidate has zero error, the first wins.
+        // non-finite group: nothing to evaluate.
+        for (int wi = tid; wi < nwords; wi += kWG)
+            gmask[wi] = (wi == 0 && m == 0.0f) ? 1u : 0u;
+        return;
+    }
+    double mn = __builtin_inf();
+    for (int k0 = tid; k0 < n; k0 += kWG) mn = fmin(mn, group_sse(sse32, tile0, r.tpg, n, k0));
+    mn = block_min(mn, lds);
+    const double thr = keep_threshold(mn, (double)r.gcount, n);
+    for (int wi = tid; wi < nwords; wi += kWG) {
+        uint32_t word = 0;
+        for (int b = 0; b < 32; ++b) {
+            int k0 = wi * 32 + b;
+            if (k0 < n && group_sse(sse32, tile0, r.tpg, n, k0) <= thr) word |= (1u << b);
+        }
+        gmask[wi] = word;
+    }
+}
+
+// ------------------------------------------------------------------- exact
+// Canonical evaluation of the kept candidates over one tile: binary32 code
+// (Eq.3), binary64 error  s*code + z - |w|, summed per thread in index order and
+// then over the workgroup in a fixed tree.  The tile's magnitudes stay in
+// registers and up to kBatch candidates share one pass.  A single-tile group
+// does its own filtering (mask in LDS) and its own argmin.
+struct BitCursor {
+    const uint32_t *words;
+    int nwords, wi;
+    uint32_t word;
+};
+__device__ inline int next_candidate(BitCursor &c)
+{
+    while (c.word == 0) {
+        if (++c.wi >= c.nwords) return -1;
+        c.word = c.words[c.wi];
+    }
+    const int b = __builtin_ctz(c.word);
+    c.word &= c.word - 1;
+    return c.wi * 32 + b + 1;
+}
+
+__device__ inline double exact_error_sq(const Pieces &q, float a)
+{
+    bool tail;
+    const float code = piece_code(q, a, tail);
+    const double s = tail ? (double)q.s2 : (double)q.s1;
+    const double z = tail ? (double)q.p : 0.0;
+    const double e = (double)code * s + z - (double)a;
+    return e * e;
+}
+
+struct ExactState {
+    double best;
+    int best_k;
+    int slot;
+};
+
+// Evaluates every kept candidate over a tile whose threads hold kEpt elements
+// each.  Candidates are taken one or two at a time (there are rarely more).
+template <int kEpt>
+__device__ inline void exact_tile(const float *__restrict__ src, int len, float m, int n, int bits,
+                                  BitCursor &cur, bool single, double *__restrict__ part,
+                                  double *lds, ExactState &st)
+{
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    // kEpt > 0: the thread's elements stay in registers; kEpt == 0 (long
+    // tiles): they are re-read for every pass (they sit in L2)
+    float a[kEpt > 0 ? kEpt : 1];
+    if (kEpt > 0) {
+#pragma unroll
+        for (int e = 0; e < kEpt; ++e) {
+            const int i = tid + e * kWG;
+            a[e] = (i < len) ? fabsf(src[i]) : 0.0f;
+        }
+    }
+    for (;;) {
+        const int k0 = next_candidate(cur);
+        if (k0 < 0) break;
+        const int k1 = next_candidate(cur);
+        const Pieces q0 = make_pieces(m, grid_point(m, k0, n), bits);
+        double acc0 = 0.0, acc1 = 0.0;
+        if (k1 < 0) {
+            if (kEpt > 0) {
+#pragma unroll
+                for (int e = 0; e < kEpt; ++e)
+                    if (tid + e * kWG < len) acc0 += exact_error_sq(q0, a[e]);
+            } else {
+                for (int i = tid; i < len; i += kWG) acc0 += exact_error_sq(q0, fabsf(src[i]));
+            }
+        } else {
+            const Pieces q1 = make_pieces(m, grid_point(m, k1, n), bits);
+            if (kEpt > 0) {
+#pragma unroll
+                for (int e = 0; e < kEpt; ++e) {
+                    if (tid + e * kWG < len) {
+                        acc0 += exact_error_sq(q0, a[e]);
+                        acc1 += exact_error_sq(q1, a[e]);
+                    }
+                }
+            } else {
+                for (int i = tid; i < len; i += kWG) {
+                    const float av = fabsf(src[i]);
+                    acc0 += exact_error_sq(q0, av);
+                    acc1 += exact_error_sq(q1, av);
+                }
+            }
+        }
+        acc0 = wave_sum(acc0);
+        acc1 = wave_sum(acc1);
+        __syncthreads();
+        if (lane == 0) { lds[wave * 2] = acc0; lds[wave * 2 + 1] = acc1; }
+        __syncthreads();
+        double s0 = lds[0], s1 = lds[1];
+        for (int w = 1; w < kWaves; ++w) { s0 += lds[w * 2]; s1 += lds[w * 2 + 1]; }
+        if (single) {
+            if (st.best_k < 0 || s0 < st.best) { st.best = s0; st.best_k = k0; }
+            if (k1 >= 0 && s1 < st.best) { st.best = s1; st.best_k = k1; }
+        } else if (tid == 0) {
+            part[st.slot] = s0;
+            if (k1 >= 0) part[st.slot + 1] = s1;
+        }
+        st.slot += (k1 >= 0) ? 2 : 1;
+    }
+}
+
+__global__ __launch_bounds__(kWG) void k_exact(Tables tb, int n, int nwords, int bits,
+                                               const float *__restrict__ gm,
+                                               const float *__restrict__ sse32,
+                                               const uint32_t *__restrict__ mask,
+                                               double *__restrict__ part64,
+                                               float *__restrict__ p_star,
+                                               float *__restrict__ m_out,
+                                               int32_t *__restrict__ k_star,
+                                               double *__restrict__ mse)
+{
+    extern __shared__ uint32_t lmask[];          // single-tile groups: ceil(n/256)*8 words
+    __shared__ double lds[kWaves * 2];
+    const int t = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    TensorRec r;
+    TileInfo ti = tile_of(tb, t, r);
+    const bool single = r.tpg == 1;
+    const float m = gm[ti.group];
+    const long long og = r.out_group + ti.group_local;
+    const bool usable = (m > 0.0f) && (m < __builtin_inff());
+
+    BitCursor cur;
+    cur.wi = -1;
+    cur.word = 0;
+    if (single) {
+        const int lwords = (n + kWG - 1) / kWG * 8;
+        if (!usable) {
+            for (int wi = tid; wi < lwords; wi += kWG) lmask[wi] = (wi == 0 && m == 0.0f) ? 1u : 0u;
+        } else {
+            const float *row = sse32 + (long long)t * n;
+            double mn = __builtin_inf();
+            for (int k0 = tid; k0 < n; k0 += kWG) mn = fmin(mn, (double)row[k0]);
+            mn = block_min(mn, lds);
+            const double thr = keep_threshold(mn, (double)r.gcount, n);
+            for (int base = 0; base < n; base += kWG) {
+                const int k0 = base + tid;
+                const bool keep = (k0 < n) && ((double)row[k0] <= thr);
+                const unsigned long long bal = __ballot(keep);
+                if (lane == 0) {
+                    lmask[(base >> 5) + wave * 2] = (uint32_t)bal;
+                    lmask[(base >> 5) + wave * 2 + 1] = (uint32_t)(bal >> 32);
+                }
+            }
+        }
+        __syncthreads();
+        cur.words = lmask;
+        cur.nwords = lwords;
+    } else {
+        cur.words = mask + (long long)ti.group * nwords;
+        cur.nwords = nwords;
+    }
+
+    double *part = single ? nullptr
+                          : part64 + (long long)(r.part_base + ti.local_tile) * n;
+    ExactState st;
+    st.best = 0.0;
+    st.best_k = -1;
+    st.slot = 0;
+    if (ti.len <= kWG)
+        exact_tile<1>(ti.src, ti.len, m, n, bits, cur, single, part, lds, st);
+    else if (ti.len <= 4 * kWG)
+        exact_tile<4>(ti.src, ti.len, m, n, bits, cur, single, part, lds, st);
+    else if (ti.len <= 10 * kWG)
+        exact_tile<10>(ti.src, ti.len, m, n, bits, cur, single, part, lds, st);
+    else
+        exact_tile<0>(ti.src, ti.len, m, n, bits, cur, single, part, lds, st);
+
+    if (single && tid == 0) {
+        m_out[og] = m;
+        if (st.best_k < 0) {
+            k_star[og] = -1;
+            p_star[og] = __builtin_nanf("");
+            mse[og] = __builtin_nan("");
+        } else {
+            k_star[og] = st.best_k;
+            p_star[og] = grid_point(m, st.best_k, n);
+            mse[og] = st.best / (double)r.gcount;
+        }
+    }
+}
+
+// ------------------------------------------------------------------- final
+// Groups spread over several tiles: add the tiles' partial sums in tile order,
+// then take the smallest sum, lowest candidate first.
+__global__ __launch_bounds__(kWG) void k_final(Tables tb, int n, int nwords,
+                                               const float *__restrict__ gm,
+                                               const uint32_t *__restrict__ mask,
+                                               const double *__restrict__ part64,
+                                               float *__restrict__ p_star,
+                                               float *__restrict__ m_out,
+                                               int32_t *__restrict__ k_star,
+                                               double *__restrict__ mse)
+{
+    __shared__ double lds[kWaves];
+    __shared__ int slot_lds[kWaves];
+    const int mg = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int tensor = find_tensor(tb.mgroup_prefix, tb.nt, mg);
+    const TensorRec r = rec_of(tb, tensor);
+    const int gl = mg - r.mgroup_base;
+    const int g = r.group_base + gl;
+    const long long og = r.out_group + gl;
+    const float m = gm[g];
+    const uint32_t *gmask = mask + (long long)g * nwords;
+    int nflag = 0;
+    for (int wi = 0; wi < nwords; ++wi) nflag += __builtin_popcount(gmask[wi]);
+    const double *part = part64 + (long long)(r.part_base + gl * r.tpg) * n;
+
+    double best = __builtin_inf();
+    int best_slot = 0x7fffffff;
+    for (int s = tid; s < nflag; s += kWG) {
+        double v = 0.0;
+        for (int j = 0; j < r.tpg; ++j) v += part[(long long)j * n + s];
+        if (v < best) { best = v; best_slot = s; }
+    }
+    // lexicographic (sum, slot) minimum over the workgroup
+    const double wbest = block_min(best, lds);
+    int cand = (best == wbest) ? best_slot : 0x7fffffff;
+    for (int off = 32; off > 0; off >>= 1) {
+        int o = __shfl_xor(cand, off, 64);
+        cand = o < cand ? o : cand;
+    }
+    __syncthreads();
+    if ((tid & 63) == 0) slot_lds[tid >> 6] = cand;
+    __syncthreads();
+    if (tid == 0) {
+        for (int i = 1; i < kWaves; ++i) cand = slot_lds[i] < cand ? slot_lds[i] : cand;
+        m_out[og] = m;
+        if (nflag == 0 || cand == 0x7fffffff) {
+            k_star[og] = -1;
+            p_star[og] = __builtin_nanf("");
+            mse[og] = __builtin_nan("");
+        } else {
+            int k = -1, seen = 0;
+            for (int wi = 0; wi < nwords && k < 0; ++wi) {
+                uint32_t word = gmask[wi];
+                int c = __builtin_popcount(word);
+                if (seen + c > cand) {
+                    for (int i = 0; i < cand - seen; ++i) word &= word - 1;
+                    k = wi * 32 + __builtin_ctz(word) + 1;
+                }
+                seen += c;
+            }
+            k_star[og] = k;
+            p_star[og] = grid_point(m, k, n);
+            mse[og] = wbest / (double)r.gcount;
+        }
+    }
+}
+
+} // namespace pwlq

@@ -1,0 +1,140 @@
+// k_search: the candidate-evaluation kernel (dominant).
+#pragma once
+
+#include "pwlq_tables.h"
+
+namespace pwlq {
+
+// One wavefront = one block of 64 candidates of one tile; lane = candidate;
+// the 16 wavefronts of a workgroup take 16 consecutive blocks of the same tile,
+// so they stream the same cache lines through one scalar cache.
+//
+// In candidate units the centre piece of candidate k has step k/L and the tail
+// piece (n-k)/L, so the position of u in steps is  t = u*(L/k)  or
+// t = (u-k)*(L/(n-k)), and the error in steps is f = t - rne(t).  Sum f^2 per
+// region, scale by step^2 at the end.  None of this depends on the group's
+// absmax.  Elements arrive as wave-uniform scalar loads (SGPR operands).
+__device__ inline float8 load8(const float *__restrict__ p)
+{
+    return *reinterpret_cast<const float8 *>(__builtin_assume_aligned(p, 32));
+}
+
+template <bool kTail>
+__device__ inline void eval8(const float8 &x, float r, float c, float &acc0, float &acc1)
+{
+#pragma unroll
+    for (int e = 0; e < kVec; e += 2) {
+        const float t0 = kTail ? __builtin_fmaf(x[e], r, c) : x[e] * r;
+        const float t1 = kTail ? __builtin_fmaf(x[e + 1], r, c) : x[e + 1] * r;
+        const float f0 = t0 - __builtin_rintf(t0);
+        const float f1 = t1 - __builtin_rintf(t1);
+        acc0 = __builtin_fmaf(f0, f0, acc0);
+        acc1 = __builtin_fmaf(f1, f1, acc1);
+    }
+}
+
+// All 64 candidates see every element of us[begin, end) in the same region.
+template <bool kTail>
+__device__ inline float zone_one_region(const float *__restrict__ us, int begin, int end,
+                                        float r, float c)
+{
+    float outer = 0.0f;
+    for (int cb = begin; cb < end; cb += kChunk) {
+        const int ce = (cb + kChunk < end) ? cb + kChunk : end;
+        float acc0 = 0.0f, acc1 = 0.0f;
+        for (int i = cb; i < ce; i += kVec) {
+            const float8 x = load8(us + i);
+            eval8<kTail>(x, r, c, acc0, acc1);
+        }
+        outer += acc0 + acc1;
+    }
+    return outer;
+}
+
+// The wavefront's own bucket: the region differs from lane to lane.  Written
+// as a branch so that the compiler runs the centre lanes and the tail lanes
+// under execution masks (cheaper than selecting three operands per lane); the
+// error is summed in candidate units.
+__device__ inline float zone_mixed(const float *__restrict__ us, int begin, int end, float kf,
+                                   float rc, float rt, float ct, float stepc, float stept)
+{
+    float outer = 0.0f;
+    for (int cb = begin; cb < end; cb += kChunk) {
+        const int ce = (cb + kChunk < end) ? cb + kChunk : end;
+        float acc = 0.0f;
+        for (int i = cb; i < ce; i += kVec) {
+            const float8 cur = load8(us + i);
+#pragma unroll
+            for (int e = 0; e < kVec; ++e) {
+                const float u = cur[e];
+                if (u > kf) {
+                    const float t = __builtin_fmaf(u, rt, ct);
+                    const float err = (t - __builtin_rintf(t)) * stept;
+                    acc = __builtin_fmaf(err, err, acc);
+                } else {
+                    const float t = u * rc;
+                    const float err = (t - __builtin_rintf(t)) * stepc;
+                    acc = __builtin_fmaf(err, err, acc);
+                }
+            }
+        }
+        outer += acc;
+    }
+    return outer;
+}
+
+__global__ __launch_bounds__(kSearchWaves * 64) void k_search(Tables tb, int n, int nblk, int bits,
+                                                              int ny,
+                                                              const int *__restrict__ offsets,
+                                                              const float *__restrict__ sorted,
+                                                              float *__restrict__ sse32)
+{
+    // Workgroup ids are dealt round-robin to the 8 XCDs.  Keep the ny
+    // workgroups of one unit (same tiles, different candidate blocks) on one
+    // XCD so its L2 serves their reads, and deal units round-robin.
+    const int wg = blockIdx.x;
+    const int xcd = wg & 7;
+    const int slot = wg >> 3;
+    const int unit = (slot / ny) * 8 + xcd;
+    const int jy = slot % ny;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int j = jy * kSearchWaves + wave;
+    if (unit >= tb.n_units || j >= nblk) return;
+
+    const int tensor = find_tensor(tb.unit_prefix, tb.nt, unit);
+    const TensorRec r = rec_of(tb, tensor);
+    const int first = r.tile_base + (unit - r.unit_base) * r.tpu;
+    int last = first + r.tpu;
+    if (last > r.tile_base + r.ntiles) last = r.tile_base + r.ntiles;
+
+    const int lane = threadIdx.x & 63;
+    int k = j * kBlk + lane + 1;
+    const bool live = k <= n;
+    if (!live) k = n;
+    const float Lf = (float)((1 << (bits - 1)) - 1);
+    const float kf = (float)k;
+    const float nk = (float)(n - k);
+    const float rc = Lf / kf;
+    const float rt = (k < n) ? Lf / nk : 0.0f;
+    const float ct = -kf * rt;
+    const float stepc = kf / Lf;
+    const float stept = nk / Lf;
+
+    for (int t = first; t < last; ++t) {
+        const int local = t - r.tile_base;
+        const int tig = local % r.tpg;
+        const int len = (tig == r.tpg - 1) ? r.last_len : r.tile_len;
+        const int padded = (len + kVec - 1) / kVec * kVec;
+        const float *us = sorted + (r.sorted_base + (long long)local * r.stride);
+        const int *off = offsets + (long long)t * (nblk + 1);
+        const int lo = off[j] & ~(kVec - 1);
+        const int hi = (off[j + 1] + kVec - 1) & ~(kVec - 1);
+        const float sc = zone_one_region<false>(us, 0, lo, rc, 0.0f);
+        const float sm = zone_mixed(us, lo, hi, kf, rc, rt, ct, stepc, stept);
+        const float st = zone_one_region<true>(us, hi, padded, rt, ct);
+        if (live)
+            sse32[(long long)t * n + (k - 1)] = (stepc * stepc) * sc + (stept * stept) * st + sm;
+    }
+}
+
+} // namespace pwlq

@@ -1,0 +1,60 @@
+// Per-call tensor table as the kernels see it.
+#pragma once
+
+#include "pwlq_device.h"
+
+namespace pwlq {
+
+typedef float float8 __attribute__((ext_vector_type(8)));
+
+// A call with one tensor carries its record in the kernel arguments (`one`)
+// and touches no table in memory; a model-level call reads `recs` and the
+// prefix arrays from the head of the workspace.
+struct Tables {
+    const TensorRec *recs;
+    const int *tile_prefix, *group_prefix, *unit_prefix, *mgroup_prefix;
+    int nt;
+    int n_units;
+    TensorRec one;
+};
+
+// Every field of a record is the same in all lanes; passing it through
+// readfirstlane tells the compiler so, which keeps loop bounds and addresses
+// derived from it in scalar registers (and the loads they feed scalar loads).
+__device__ inline int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ inline long long uni(long long v)
+{
+    unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(v & 0xffffffffLL));
+    int hi = __builtin_amdgcn_readfirstlane((int)(v >> 32));
+    return ((long long)hi << 32) | (long long)lo;
+}
+__device__ inline TensorRec rec_of(const Tables &tb, int i)
+{
+    TensorRec r = (tb.nt == 1) ? tb.one : tb.recs[i];
+    r.w = reinterpret_cast<const float *>(uni((long long)reinterpret_cast<uintptr_t>(r.w)));
+    r.gcount = uni(r.gcount);
+    r.sorted_base = uni(r.sorted_base);
+    r.out_elem = uni(r.out_elem);
+    r.out_group = uni(r.out_group);
+    r.tile_len = uni(r.tile_len);
+    r.last_len = uni(r.last_len);
+    r.tpg = uni(r.tpg);
+    r.stride = uni(r.stride);
+    r.tpu = uni(r.tpu);
+    r.part_base = uni(r.part_base);
+    r.tile_base = uni(r.tile_base);
+    r.group_base = uni(r.group_base);
+    r.unit_base = uni(r.unit_base);
+    r.mgroup_base = uni(r.mgroup_base);
+    r.ntiles = uni(r.ntiles);
+    r.ngroups = uni(r.ngroups);
+    return r;
+}
+__device__ inline TileInfo tile_of(const Tables &tb, int t, TensorRec &r)
+{
+    const int tensor = find_tensor(tb.tile_prefix, tb.nt, t);
+    r = rec_of(tb, tensor);
+    return tile_info(r, tensor, t);
+}
+
+} // namespace pwlq
