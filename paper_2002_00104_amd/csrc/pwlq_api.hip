@@ -40,7 +40,7 @@ struct Plan {
     int n = 0, nblk = 0, nwords = 0;
     // workspace offsets in bytes
     size_t off_recs = 0, off_prefix = 0, off_tile_max = 0, off_gm = 0, off_offsets = 0,
-           off_sorted = 0, off_sse32 = 0, off_mask = 0, off_part = 0, total = 0;
+           off_sorted = 0, off_sse32 = 0, off_mask = 0, off_part = 0, off_gsum = 0, total = 0;
 };
 
 int check_common(int bits, int mode)
@@ -91,6 +91,14 @@ int build_plan(Plan &pl, const pwlq_tensor_desc *desc, int n_tensors, int n_cand
         r.tpu = std::max(1, kUnitElems / r.tile_len);
         tmp[i] = r;
         order[i] = {i, r.tile_len};
+    }
+    // a search workgroup walks tpu tiles one after the other; keep enough
+    // workgroups to fill the chip when the call is small
+    {
+        long long total_tiles = 0;
+        for (const TensorRec &r : tmp) total_tiles += r.ntiles;
+        const int cap = (int)std::max(1LL, total_tiles / kMinUnits);
+        for (TensorRec &r : tmp) r.tpu = std::min(r.tpu, cap);
     }
     // longest tiles first: the search kernel's workgroups are dispatched in
     // index order, so the big items start early and the small ones fill gaps
@@ -146,6 +154,7 @@ int build_plan(Plan &pl, const pwlq_tensor_desc *desc, int n_tensors, int n_cand
         pl.off_sse32 = take(sizeof(float) * (size_t)tiles * (size_t)n_cand);
         pl.off_mask = take(sizeof(uint32_t) * (size_t)groups * (size_t)pl.nwords);
         pl.off_part = take(sizeof(double) * (size_t)parts * (size_t)n_cand);
+        pl.off_gsum = take(sizeof(double) * (size_t)mgroups * (size_t)n_cand);
     }
     pl.total = off;
     return PWLQ_OK;
@@ -231,6 +240,12 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
     if (rc) return rc;
     rc = check_workspace(pl, workspace, workspace_bytes);
     if (rc) return rc;
+    // every limit is checked before the first launch: a failing call enqueues nothing
+    const int ny = (pl.nblk + kSearchWaves - 1) / kSearchWaves;
+    const long long units_padded = (pl.n_units + 7) / 8 * 8;
+    const long long wgs = units_padded * ny;
+    if (wgs > 0x7fffffffLL) return fail(PWLQ_EINVAL, "search grid too large");
+    if (pl.n_mgroups > 65535) return fail(PWLQ_EINVAL, "too many groups longer than one tile");
 
     hipStream_t stream = (hipStream_t)stream_v;
     char *ws = (char *)workspace;
@@ -244,6 +259,7 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
     float *sse32 = (float *)(ws + pl.off_sse32);
     uint32_t *mask = (uint32_t *)(ws + pl.off_mask);
     double *part64 = (double *)(ws + pl.off_part);
+    double *gsum = (double *)(ws + pl.off_gsum);
 
     const int NT = (int)pl.n_tiles;
     if (pl.n_mgroups > 0) k_tile_absmax<<<NT, kWG, 0, stream>>>(tb, tile_max);
@@ -254,16 +270,15 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
         k_prep<false><<<NT, kWG, sizeof(int) * pl.nblk, stream>>>(
             tb, n_cand, pl.nblk, tile_max, gm, offsets, sorted);
     }
-    const int ny = (pl.nblk + kSearchWaves - 1) / kSearchWaves;
-    const long long units_padded = (pl.n_units + 7) / 8 * 8;
-    const long long wgs = units_padded * ny;
-    if (wgs > 0x7fffffffLL) return fail(PWLQ_EINVAL, "search grid too large");
     profile_mark(0, stream);
     k_search<<<(unsigned)wgs, kSearchWaves * 64, 0, stream>>>(tb, n_cand, pl.nblk, bits, ny,
                                                 offsets, sorted, sse32);
     profile_mark(1, stream);
-    if (pl.n_mgroups > 0)
-        k_flag<<<(int)pl.n_mgroups, kWG, 0, stream>>>(tb, n_cand, pl.nwords, gm, sse32, mask);
+    if (pl.n_mgroups > 0) {
+        k_group_sum<<<dim3((n_cand + kWG - 1) / kWG, (unsigned)pl.n_mgroups), kWG, 0, stream>>>(
+            tb, n_cand, sse32, gsum);
+        k_flag<<<(int)pl.n_mgroups, kWG, 0, stream>>>(tb, n_cand, pl.nwords, gm, gsum, mask);
+    }
     const size_t lmask_bytes = sizeof(uint32_t) * 8 * (size_t)((n_cand + kWG - 1) / kWG);
     k_exact<<<NT, kWG, lmask_bytes, stream>>>(tb, n_cand, pl.nwords, bits, gm, sse32, mask, part64,
                                               p_star, m_out, k_star, mse);

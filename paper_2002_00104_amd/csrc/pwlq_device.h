@@ -18,6 +18,7 @@ constexpr int kSearchWaves = 16;  // wavefronts (candidate blocks) per search wo
 constexpr int kTileMax = 8192;    // longest run of a group handled by one workgroup
 constexpr int kPerThread = kTileMax / kWG;  // elements of a tile held by one thread
 constexpr int kUnitElems = 4096;  // small tiles are batched up to about this many elements
+constexpr int kMinUnits = 4096;   // ... unless that would leave fewer search units than this
 constexpr int kVec = 8;           // elements per scalar vector load in the search loop
 constexpr int kChunk = 128;       // elements per inner fp32 accumulation chunk
 

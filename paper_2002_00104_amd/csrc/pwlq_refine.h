@@ -16,30 +16,41 @@ __device__ inline double keep_threshold(double mn, double count, int n)
     return mn + 2.0 * (3e-5 * mn + 2.0 * eps * sqrt(count * mn) + count * eps * eps);
 }
 
-__device__ inline double group_sse(const float *__restrict__ sse32, long long tile0, int tpg,
-                                   int n, int k0)
+// Groups spread over several tiles, step 1: add the tiles' binary32 sums in
+// binary64, in tile order.  One thread per (group, candidate); consecutive
+// threads read consecutive candidates of the same tile row.
+__global__ __launch_bounds__(kWG) void k_group_sum(Tables tb, int n,
+                                                   const float *__restrict__ sse32,
+                                                   double *__restrict__ gsum)
 {
+    const int mg = blockIdx.y;
+    const int k0 = blockIdx.x * kWG + threadIdx.x;
+    const int tensor = find_tensor(tb.mgroup_prefix, tb.nt, mg);
+    const TensorRec r = rec_of(tb, tensor);
+    const int gl = mg - r.mgroup_base;
+    const long long tile0 = r.tile_base + (long long)gl * r.tpg;
+    if (k0 >= n) return;
     double v = 0.0;
-    for (int j = 0; j < tpg; ++j) v += (double)sse32[(tile0 + j) * n + k0];
-    return v;
+    for (int j = 0; j < r.tpg; ++j) v += (double)sse32[(tile0 + j) * n + k0];
+    gsum[(long long)mg * n + k0] = v;
 }
 
-// Groups spread over several tiles: tile sums added in binary64, kept
-// candidates written as a bit mask (bit k-1 of the group's row).
+// Step 2: the group's minimum and the bit mask of kept candidates (bit k-1).
 __global__ __launch_bounds__(kWG) void k_flag(Tables tb, int n, int nwords,
                                               const float *__restrict__ gm,
-                                              const float *__restrict__ sse32,
+                                              const double *__restrict__ gsum,
                                               uint32_t *__restrict__ mask)
 {
     __shared__ double lds[kWaves];
     const int mg = blockIdx.x;
     const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
     const int tensor = find_tensor(tb.mgroup_prefix, tb.nt, mg);
     const TensorRec r = rec_of(tb, tensor);
-    const int gl = mg - r.mgroup_base;
-    const int g = r.group_base + gl;
-    const long long tile0 = r.tile_base + (long long)gl * r.tpg;
+    const int g = r.group_base + (mg - r.mgroup_base);
     uint32_t *gmask = mask + (long long)g * nwords;
+    const double *row = gsum + (long long)mg * n;
     const float m = gm[g];
     if (!(m > 0.0f) || !(m < __builtin_inff())) {
         // all-zero group: every candidate has zero error, the first wins.
@@ -49,16 +60,18 @@ __global__ __launch_bounds__(kWG) void k_flag(Tables tb, int n, int nwords,
         return;
     }
     double mn = __builtin_inf();
-    for (int k0 = tid; k0 < n; k0 += kWG) mn = fmin(mn, group_sse(sse32, tile0, r.tpg, n, k0));
+    for (int k0 = tid; k0 < n; k0 += kWG) mn = fmin(mn, row[k0]);
     mn = block_min(mn, lds);
     const double thr = keep_threshold(mn, (double)r.gcount, n);
-    for (int wi = tid; wi < nwords; wi += kWG) {
-        uint32_t word = 0;
-        for (int b = 0; b < 32; ++b) {
-            int k0 = wi * 32 + b;
-            if (k0 < n && group_sse(sse32, tile0, r.tpg, n, k0) <= thr) word |= (1u << b);
+    for (int base = 0; base < n; base += kWG) {
+        const int k0 = base + tid;
+        const bool keep = (k0 < n) && (row[k0] <= thr);
+        const unsigned long long bal = __ballot(keep);
+        const int w0 = (base >> 5) + wave * 2;
+        if (lane == 0) {
+            if (w0 < nwords) gmask[w0] = (uint32_t)bal;
+            if (w0 + 1 < nwords) gmask[w0 + 1] = (uint32_t)(bal >> 32);
         }
-        gmask[wi] = word;
     }
 }
 
