@@ -81,25 +81,78 @@ __device__ inline TileInfo tile_info(const TensorRec &r, int tensor, int t)
 }
 
 // ---- wavefront / workgroup reductions (fixed order, so results are repeatable)
+// Built on DPP row shifts and row broadcasts: four shift-and-combine steps scan
+// each row of 16 lanes, row_bcast:15 carries a row's total into the next row
+// (rows 1 and 3), row_bcast:31 carries lane 31 into rows 2 and 3.  After the six
+// steps lane i holds the combination of lanes 0..i, so lane 63 holds the total.
+// A lane with no source keeps `old`.
+template <int kCtrl, int kRows>
+__device__ inline int dpp_i32(int old, int v)
+{
+    return __builtin_amdgcn_update_dpp(old, v, kCtrl, kRows, 0xf, false);
+}
+template <int kCtrl, int kRows>
+__device__ inline float dpp_f32(float old, float v)
+{
+    return __int_as_float(dpp_i32<kCtrl, kRows>(__float_as_int(old), __float_as_int(v)));
+}
+template <int kCtrl, int kRows>
+__device__ inline double dpp_f64(double old, double v)
+{
+    const int lo = dpp_i32<kCtrl, kRows>(__double2loint(old), __double2loint(v));
+    const int hi = dpp_i32<kCtrl, kRows>(__double2hiint(old), __double2hiint(v));
+    return __hiloint2double(hi, lo);
+}
+__device__ inline double lane63(double v)
+{
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), 63),
+                            __builtin_amdgcn_readlane(__double2loint(v), 63));
+}
+
+// inclusive prefix sum over the 64 lanes of a wavefront
+__device__ inline int wave_scan_incl(int v)
+{
+    v += dpp_i32<0x111, 0xf>(0, v);
+    v += dpp_i32<0x112, 0xf>(0, v);
+    v += dpp_i32<0x114, 0xf>(0, v);
+    v += dpp_i32<0x118, 0xf>(0, v);
+    v += dpp_i32<0x142, 0xa>(0, v);
+    v += dpp_i32<0x143, 0xc>(0, v);
+    return v;
+}
 __device__ inline float wave_max(float v)
 {
-    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
-    return v;
+    v = fmaxf(v, dpp_f32<0x111, 0xf>(v, v));
+    v = fmaxf(v, dpp_f32<0x112, 0xf>(v, v));
+    v = fmaxf(v, dpp_f32<0x114, 0xf>(v, v));
+    v = fmaxf(v, dpp_f32<0x118, 0xf>(v, v));
+    v = fmaxf(v, dpp_f32<0x142, 0xa>(v, v));
+    v = fmaxf(v, dpp_f32<0x143, 0xc>(v, v));
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 __device__ inline double wave_sum(double v)
 {
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
+    v += dpp_f64<0x111, 0xf>(0.0, v);
+    v += dpp_f64<0x112, 0xf>(0.0, v);
+    v += dpp_f64<0x114, 0xf>(0.0, v);
+    v += dpp_f64<0x118, 0xf>(0.0, v);
+    v += dpp_f64<0x142, 0xa>(0.0, v);
+    v += dpp_f64<0x143, 0xc>(0.0, v);
+    return lane63(v);
 }
 __device__ inline double wave_min(double v)
 {
-    for (int off = 32; off > 0; off >>= 1) v = fmin(v, __shfl_xor(v, off, 64));
-    return v;
+    v = fmin(v, dpp_f64<0x111, 0xf>(v, v));
+    v = fmin(v, dpp_f64<0x112, 0xf>(v, v));
+    v = fmin(v, dpp_f64<0x114, 0xf>(v, v));
+    v = fmin(v, dpp_f64<0x118, 0xf>(v, v));
+    v = fmin(v, dpp_f64<0x142, 0xa>(v, v));
+    v = fmin(v, dpp_f64<0x143, 0xc>(v, v));
+    return lane63(v);
 }
 __device__ inline int wave_or(int v)
 {
-    for (int off = 32; off > 0; off >>= 1) v |= __shfl_xor(v, off, 64);
-    return v;
+    return __ballot(v != 0) != 0ull;
 }
 
 // Sum over the workgroup, returned to every thread.  `lds` holds kWaves doubles.

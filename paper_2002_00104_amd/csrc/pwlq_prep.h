@@ -50,17 +50,6 @@ __device__ inline int bucket_of(float u)
     return (kc - 1) >> 6;
 }
 
-// inclusive prefix sum over the 64 lanes of a wavefront
-__device__ inline int wave_scan_incl(int v)
-{
-    const int lane = threadIdx.x & 63;
-    for (int off = 1; off < 64; off <<= 1) {
-        int o = __shfl_up(v, off, 64);
-        if (lane >= off) v += o;
-    }
-    return v;
-}
-
 // Sorted layout of one tile: [pad zeros][bucket 0][bucket 1]...; the padded
 // length is a multiple of kVec and off[j] is the start of bucket j.  The tile's elements stay in registers between the passes, so the
 // weights are read from memory once.  kPrivate (at most 32 buckets): every
@@ -135,8 +124,9 @@ __global__ __launch_bounds__(kWG) void k_prep(Tables tb, int n, int nblk,
             const float u = usable ? to_units(a[e], m, nf) : 0.0f;
             a[e] = u;
             const int b = bucket_of(u);
-            if (kPrivate) hist[b * kWG + tid] += 1;
-            else atomicAdd(&hist[b], 1);
+            // fire-and-forget LDS add: the column is private, the atomic form only keeps
+            // the updates pipelined instead of read-modify-write round trips
+            atomicAdd(&hist[kPrivate ? b * kWG + tid : b], 1);
         }
     }
 
@@ -192,12 +182,8 @@ __global__ __launch_bounds__(kWG) void k_prep(Tables tb, int n, int nblk,
             const float u = a[e];
             const int b = bucket_of(u);
             int pos;
-            if (kPrivate) {
-                pos = wtot[b * kWaves + wave] + hist[b * kWG + tid];
-                hist[b * kWG + tid] += 1;
-            } else {
-                pos = atomicAdd(&hist[b], 1);
-            }
+            if (kPrivate) pos = wtot[b * kWaves + wave] + atomicAdd(&hist[b * kWG + tid], 1);
+            else pos = atomicAdd(&hist[b], 1);
             out[pad + pos] = u;
         }
     }
