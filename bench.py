@@ -34,6 +34,22 @@ LANE_OPS_PER_EVAL = 9
 PEAK_LANE_OPS = 256 * 128 * 2.4e9
 
 
+def _measured_traffic(workload: int, kernel: str):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter runs
+    (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy), or None if this workload
+    was not measured."""
+    path = os.path.join(ROOT, "paper_2002_00104_amd", "measured_traffic.json")
+    try:
+        with open(path) as f:
+            m = json.load(f)
+        if m.get("workload") != workload:
+            return None
+        k = m["kernels"][kernel]
+        return k["read_bytes"] + k["written_bytes"]
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -41,6 +57,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", type=int, default=2, help="1..5 (default 2: ResNet-50 shapes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 256 MiB device copy three times (scales the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path "
@@ -56,6 +75,14 @@ def main() -> int:
         print("bench.py needs a GPU", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        a = torch.ones(64 << 20, dtype=torch.float32, device="cuda")       # 256 MiB
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_each_way": a.numel() * 4, "launches": 3}))
+        return 0
     wl = synth.workload(args.workload)
     host = list(wl.tensors())
     dev = [torch.from_numpy(t).cuda() for t in host]
@@ -133,7 +160,7 @@ def main() -> int:
             "peak": PEAK_LANE_OPS / 1e12,
             "unit": "Tlane-op/s (fp32 VALU lane-instructions; 9 per evaluation, algorithmic)",
             "frac": achieved / PEAK_LANE_OPS,
-            "traffic": None,
+            "traffic": _measured_traffic(wl.index, pwlq.kernel_name(0)),
             "kernel_ms": ks,
             "kernel_evals_per_s": evals / (ks * 1e-3),
         },

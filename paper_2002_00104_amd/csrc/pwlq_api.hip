@@ -263,11 +263,14 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
 
     const int NT = (int)pl.n_tiles;
     if (pl.n_mgroups > 0) k_tile_absmax<<<NT, kWG, 0, stream>>>(tb, tile_max);
+    int longest = 0;
+    for (const TensorRec &r : pl.recs) longest = std::max(longest, r.tile_len);
+    const size_t stage_bytes = sizeof(float) * (size_t)((longest + kVec - 1) / kVec * kVec);
     if (pl.nblk <= 32) {
-        k_prep<true><<<NT, kWG, sizeof(int) * pl.nblk * kWG, stream>>>(
+        k_prep<true><<<NT, kWG, sizeof(int) * ((pl.nblk + 1) / 2) * kWG + stage_bytes, stream>>>(
             tb, n_cand, pl.nblk, tile_max, gm, offsets, sorted);
     } else {
-        k_prep<false><<<NT, kWG, sizeof(int) * pl.nblk, stream>>>(
+        k_prep<false><<<NT, kWG, sizeof(int) * pl.nblk + stage_bytes, stream>>>(
             tb, n_cand, pl.nblk, tile_max, gm, offsets, sorted);
     }
     profile_mark(0, stream);

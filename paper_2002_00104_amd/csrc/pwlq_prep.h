@@ -51,8 +51,9 @@ __device__ inline int bucket_of(float u)
 }
 
 // Sorted layout of one tile: [pad zeros][bucket 0][bucket 1]...; the padded
-// length is a multiple of kVec and off[j] is the start of bucket j.  The tile's elements stay in registers between the passes, so the
-// weights are read from memory once.  kPrivate (at most 32 buckets): every
+// length is a multiple of kVec and off[j] is the start of bucket j.  The tile's
+// elements stay in registers between the passes, so the weights are read from
+// memory once.  kPrivate (at most 32 buckets): every
 // thread counts into its own histogram column and positions are assigned in
 // (bucket, thread, element) order, so the layout is repeatable; otherwise LDS
 // integer atomics assign positions inside a bucket in arrival order.
@@ -63,10 +64,11 @@ __global__ __launch_bounds__(kWG) void k_prep(Tables tb, int n, int nblk,
                                                int *__restrict__ offsets,
                                                float *__restrict__ sorted)
 {
-    extern __shared__ int hist[];     // kPrivate: [nblk][kWG], else [nblk]
+    extern __shared__ int hist[];     // kPrivate: [ceil(nblk/2)][kWG] packed pairs, else [nblk]
     __shared__ float redm[kWaves];
     __shared__ int redbad[kWaves];
     __shared__ int wtot[32 * kWaves];
+    __shared__ int wpair[16 * kWaves];
     __shared__ int scan_lds[kWaves];
     const int t = blockIdx.x;
     const int tid = threadIdx.x;
@@ -116,7 +118,11 @@ __global__ __launch_bounds__(kWG) void k_prep(Tables tb, int n, int nblk,
     int *off = offsets + (long long)t * (nblk + 1);
 
     // pass A: units and histogram
-    if (kPrivate) for (int b = 0; b < nblk; ++b) hist[b * kWG + tid] = 0;
+    // kPrivate: a thread's counts of buckets 2w and 2w+1 share one word (16 bits
+    // each: a thread holds at most 32 elements and a wavefront 2048, so neither
+    // the counts nor their prefix sums carry into the other half)
+    const int nb2 = (nblk + 1) >> 1;
+    if (kPrivate) for (int w = 0; w < nb2; ++w) hist[w * kWG + tid] = 0;
 #pragma unroll
     for (int e = 0; e < kPerThread; ++e) {
         const int i = tid + e * kWG;
@@ -126,17 +132,18 @@ __global__ __launch_bounds__(kWG) void k_prep(Tables tb, int n, int nblk,
             const int b = bucket_of(u);
             // fire-and-forget LDS add: the column is private, the atomic form only keeps
             // the updates pipelined instead of read-modify-write round trips
-            atomicAdd(&hist[kPrivate ? b * kWG + tid : b], 1);
+            if (kPrivate) atomicAdd(&hist[(b >> 1) * kWG + tid], 1 << (16 * (b & 1)));
+            else atomicAdd(&hist[b], 1);
         }
     }
 
     // exclusive positions
     if (kPrivate) {
-        for (int b = 0; b < nblk; ++b) {
-            const int c = hist[b * kWG + tid];
-            const int incl = wave_scan_incl(c);
-            hist[b * kWG + tid] = incl - c;                 // exclusive inside the wavefront
-            if (lane == 63) wtot[b * kWaves + wave] = incl;
+        for (int w = 0; w < nb2; ++w) {
+            const int c = hist[w * kWG + tid];
+            const int incl = wave_scan_incl(c);             // both halves at once
+            hist[w * kWG + tid] = incl - c;                 // exclusive inside the wavefront
+            if (lane == 63) wpair[w * kWaves + wave] = incl;
         }
         __syncthreads();
         if (wave == 0) {
@@ -144,7 +151,9 @@ __global__ __launch_bounds__(kWG) void k_prep(Tables tb, int n, int nblk,
             int tot = 0;
 #pragma unroll
             for (int i = 0; i < kWaves; ++i) {
-                w[i] = (lane < nblk) ? wtot[lane * kWaves + i] : 0;
+                w[i] = (lane < nblk)
+                           ? (wpair[(lane >> 1) * kWaves + i] >> (16 * (lane & 1))) & 0xffff
+                           : 0;
                 tot += w[i];
             }
             int run = wave_scan_incl(tot) - tot;            // first position of bucket `lane`
@@ -171,10 +180,12 @@ __global__ __launch_bounds__(kWG) void k_prep(Tables tb, int n, int nblk,
         for (int i = lo; i < hi; ++i) { int v = hist[i]; hist[i] = run; off[i] = pad + run; run += v; }
         if (tid == 0) off[nblk] = pad + len;
     }
-    for (int i = tid; i < pad; i += kWG) out[i] = 0.0f;
+    // pass B: scatter into the LDS image of the sorted tile, then write it out
+    // with full-width coalesced stores (scattered 4-byte stores to memory cost
+    // one transaction each)
+    float *stage = reinterpret_cast<float *>(hist + (kPrivate ? nb2 * kWG : nblk));
+    for (int i = tid; i < pad; i += kWG) stage[i] = 0.0f;
     __syncthreads();
-
-    // pass B: scatter
 #pragma unroll
     for (int e = 0; e < kPerThread; ++e) {
         const int i = tid + e * kWG;
@@ -182,11 +193,20 @@ __global__ __launch_bounds__(kWG) void k_prep(Tables tb, int n, int nblk,
             const float u = a[e];
             const int b = bucket_of(u);
             int pos;
-            if (kPrivate) pos = wtot[b * kWaves + wave] + atomicAdd(&hist[b * kWG + tid], 1);
-            else pos = atomicAdd(&hist[b], 1);
-            out[pad + pos] = u;
+            if (kPrivate) {
+                const int sh = 16 * (b & 1);
+                const int old = atomicAdd(&hist[(b >> 1) * kWG + tid], 1 << sh);
+                pos = wtot[b * kWaves + wave] + ((old >> sh) & 0xffff);
+            }
+            else {
+                pos = atomicAdd(&hist[b], 1);
+            }
+            stage[pad + pos] = u;
         }
     }
+    __syncthreads();
+    for (int i = tid * 4; i < padded; i += kWG * 4)
+        *reinterpret_cast<float4 *>(out + i) = *reinterpret_cast<const float4 *>(stage + i);
 }
 
 } // namespace pwlq
