@@ -152,7 +152,7 @@ int build_plan(Plan &pl, const pwlq_tensor_desc *desc, int n_tensors, int n_cand
         pl.off_offsets = take(sizeof(int) * (size_t)tiles * (size_t)(pl.nblk + 1));
         pl.off_sorted = take(sizeof(float) * (size_t)sorted);
         pl.off_sse32 = take(sizeof(float) * (size_t)tiles * (size_t)n_cand);
-        pl.off_mask = take(sizeof(uint32_t) * (size_t)groups * (size_t)pl.nwords);
+        pl.off_mask = take(sizeof(int) * (size_t)mgroups * (size_t)(n_cand + 1));
         pl.off_part = take(sizeof(double) * (size_t)parts * (size_t)n_cand);
         pl.off_gsum = take(sizeof(double) * (size_t)mgroups * (size_t)n_cand);
     }
@@ -257,7 +257,7 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
     int *offsets = (int *)(ws + pl.off_offsets);
     float *sorted = (float *)(ws + pl.off_sorted);
     float *sse32 = (float *)(ws + pl.off_sse32);
-    uint32_t *mask = (uint32_t *)(ws + pl.off_mask);
+    int *klist = (int *)(ws + pl.off_mask);
     double *part64 = (double *)(ws + pl.off_part);
     double *gsum = (double *)(ws + pl.off_gsum);
 
@@ -280,14 +280,13 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
     if (pl.n_mgroups > 0) {
         k_group_sum<<<dim3((n_cand + kWG - 1) / kWG, (unsigned)pl.n_mgroups), kWG, 0, stream>>>(
             tb, n_cand, sse32, gsum);
-        k_flag<<<(int)pl.n_mgroups, kWG, 0, stream>>>(tb, n_cand, pl.nwords, gm, gsum, mask);
+        k_flag<<<(int)pl.n_mgroups, kWG, 0, stream>>>(tb, n_cand, gm, gsum, klist);
     }
-    const size_t lmask_bytes = sizeof(uint32_t) * 8 * (size_t)((n_cand + kWG - 1) / kWG);
-    k_exact<<<NT, kWG, lmask_bytes, stream>>>(tb, n_cand, pl.nwords, bits, gm, sse32, mask, part64,
-                                              p_star, m_out, k_star, mse);
+    k_exact<<<NT, kWG, 0, stream>>>(tb, n_cand, bits, gm, sse32, klist, part64, p_star, m_out, k_star,
+                                    mse);
     if (pl.n_mgroups > 0)
-        k_final<<<(int)pl.n_mgroups, kWG, 0, stream>>>(tb, n_cand, pl.nwords, gm, mask, part64,
-                                                       p_star, m_out, k_star, mse);
+        k_final<<<(int)pl.n_mgroups, kWG, 0, stream>>>(tb, n_cand, gm, klist, part64, p_star, m_out,
+                                                       k_star, mse);
     g_last_tiles = pl.n_tiles;
     g_last_groups = pl.n_groups;
     g_last_units = pl.n_units;

@@ -1,4 +1,5 @@
-// k_flag, k_exact, k_final: filter by the binary32 SSE, exact binary64 re-evaluation, argmin.
+// k_group_sum, k_flag, k_exact, k_final: filter by the binary32 SSE, exact
+// binary64 re-evaluation of the kept candidates, argmin.
 #pragma once
 
 #include "pwlq_tables.h"
@@ -35,13 +36,15 @@ __global__ __launch_bounds__(kWG) void k_group_sum(Tables tb, int n,
     gsum[(long long)mg * n + k0] = v;
 }
 
-// Step 2: the group's minimum and the bit mask of kept candidates (bit k-1).
-__global__ __launch_bounds__(kWG) void k_flag(Tables tb, int n, int nwords,
+// Step 2: the group's minimum and the ascending list of kept candidates:
+// klist[mg][0] = count, klist[mg][1..count] = candidates (1-based).
+__global__ __launch_bounds__(kWG) void k_flag(Tables tb, int n,
                                               const float *__restrict__ gm,
                                               const double *__restrict__ gsum,
-                                              uint32_t *__restrict__ mask)
+                                              int *__restrict__ klist)
 {
     __shared__ double lds[kWaves];
+    __shared__ int wcount[kWaves];
     const int mg = blockIdx.x;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -49,54 +52,42 @@ __global__ __launch_bounds__(kWG) void k_flag(Tables tb, int n, int nwords,
     const int tensor = find_tensor(tb.mgroup_prefix, tb.nt, mg);
     const TensorRec r = rec_of(tb, tensor);
     const int g = r.group_base + (mg - r.mgroup_base);
-    uint32_t *gmask = mask + (long long)g * nwords;
+    int *list = klist + (long long)mg * (n + 1);
     const double *row = gsum + (long long)mg * n;
     const float m = gm[g];
     if (!(m > 0.0f) || !(m < __builtin_inff())) {
         // all-zero group: every candidate has zero error, the first wins.
         // non-finite group: nothing to evaluate.
-        for (int wi = tid; wi < nwords; wi += kWG)
-            gmask[wi] = (wi == 0 && m == 0.0f) ? 1u : 0u;
+        if (tid == 0) {
+            list[0] = (m == 0.0f) ? 1 : 0;
+            list[1] = 1;
+        }
         return;
     }
     double mn = __builtin_inf();
     for (int k0 = tid; k0 < n; k0 += kWG) mn = fmin(mn, row[k0]);
     mn = block_min(mn, lds);
     const double thr = keep_threshold(mn, (double)r.gcount, n);
+    int total = 0;
     for (int base = 0; base < n; base += kWG) {
         const int k0 = base + tid;
         const bool keep = (k0 < n) && (row[k0] <= thr);
         const unsigned long long bal = __ballot(keep);
-        const int w0 = (base >> 5) + wave * 2;
-        if (lane == 0) {
-            if (w0 < nwords) gmask[w0] = (uint32_t)bal;
-            if (w0 + 1 < nwords) gmask[w0 + 1] = (uint32_t)(bal >> 32);
-        }
+        __syncthreads();
+        if (lane == 0) wcount[wave] = __builtin_popcountll(bal);
+        __syncthreads();
+        int before = total;
+        for (int w = 0; w < wave; ++w) before += wcount[w];
+        if (keep) list[1 + before + __builtin_popcountll(bal & ((1ull << lane) - 1ull))] = k0 + 1;
+        for (int w = 0; w < kWaves; ++w) total += wcount[w];
     }
+    if (tid == 0) list[0] = total;
 }
 
 // ------------------------------------------------------------------- exact
 // Canonical evaluation of the kept candidates over one tile: binary32 code
 // (Eq.3), binary64 error  s*code + z - |w|, summed per thread in index order and
-// then over the workgroup in a fixed tree.  The tile's magnitudes stay in
-// registers and up to kBatch candidates share one pass.  A single-tile group
-// does its own filtering (mask in LDS) and its own argmin.
-struct BitCursor {
-    const uint32_t *words;
-    int nwords, wi;
-    uint32_t word;
-};
-__device__ inline int next_candidate(BitCursor &c)
-{
-    while (c.word == 0) {
-        if (++c.wi >= c.nwords) return -1;
-        c.word = c.words[c.wi];
-    }
-    const int b = __builtin_ctz(c.word);
-    c.word &= c.word - 1;
-    return c.wi * 32 + b + 1;
-}
-
+// then over the workgroup in a fixed order.
 __device__ inline double exact_error_sq(const Pieces &q, float a)
 {
     bool tail;
@@ -110,21 +101,21 @@ __device__ inline double exact_error_sq(const Pieces &q, float a)
 struct ExactState {
     double best;
     int best_k;
-    int slot;
 };
 
-// Evaluates every kept candidate over a tile whose threads hold kEpt elements
-// each.  Candidates are taken one or two at a time (there are rarely more).
+// Evaluates list[0..count) over a tile whose threads hold kEpt elements each
+// (kEpt == 0: long tile, re-read from memory for every pass).  Candidates are
+// taken one or two at a time (there are rarely more).  Single-tile groups keep
+// the lexicographic (sum, k) minimum, so the order of the list does not matter;
+// tiles of longer groups store the sums in list order.
 template <int kEpt>
 __device__ inline void exact_tile(const float *__restrict__ src, int len, float m, int n, int bits,
-                                  BitCursor &cur, bool single, double *__restrict__ part,
-                                  double *lds, ExactState &st)
+                                  const int *list, int count, bool single,
+                                  double *__restrict__ part, double *lds, ExactState &st)
 {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    // kEpt > 0: the thread's elements stay in registers; kEpt == 0 (long
-    // tiles): they are re-read for every pass (they sit in L2)
     float a[kEpt > 0 ? kEpt : 1];
     if (kEpt > 0) {
 #pragma unroll
@@ -133,10 +124,9 @@ __device__ inline void exact_tile(const float *__restrict__ src, int len, float 
             a[e] = (i < len) ? fabsf(src[i]) : 0.0f;
         }
     }
-    for (;;) {
-        const int k0 = next_candidate(cur);
-        if (k0 < 0) break;
-        const int k1 = next_candidate(cur);
+    for (int c = 0; c < count; c += 2) {
+        const int k0 = list[c];
+        const int k1 = (c + 1 < count) ? list[c + 1] : -1;
         const Pieces q0 = make_pieces(m, grid_point(m, k0, n), bits);
         double acc0 = 0.0, acc1 = 0.0;
         if (k1 < 0) {
@@ -173,86 +163,92 @@ __device__ inline void exact_tile(const float *__restrict__ src, int len, float 
         double s0 = lds[0], s1 = lds[1];
         for (int w = 1; w < kWaves; ++w) { s0 += lds[w * 2]; s1 += lds[w * 2 + 1]; }
         if (single) {
-            if (st.best_k < 0 || s0 < st.best) { st.best = s0; st.best_k = k0; }
-            if (k1 >= 0 && s1 < st.best) { st.best = s1; st.best_k = k1; }
+            if (st.best_k < 0 || s0 < st.best || (s0 == st.best && k0 < st.best_k)) {
+                st.best = s0;
+                st.best_k = k0;
+            }
+            if (k1 >= 0 && (s1 < st.best || (s1 == st.best && k1 < st.best_k))) {
+                st.best = s1;
+                st.best_k = k1;
+            }
         } else if (tid == 0) {
-            part[st.slot] = s0;
-            if (k1 >= 0) part[st.slot + 1] = s1;
+            part[c] = s0;
+            if (k1 >= 0) part[c + 1] = s1;
         }
-        st.slot += (k1 >= 0) ? 2 : 1;
     }
 }
 
-__global__ __launch_bounds__(kWG) void k_exact(Tables tb, int n, int nwords, int bits,
+__device__ inline void exact_dispatch(const float *__restrict__ src, int len, float m, int n,
+                                      int bits, const int *list, int count, bool single,
+                                      double *__restrict__ part, double *lds, ExactState &st)
+{
+    if (len <= kWG) exact_tile<1>(src, len, m, n, bits, list, count, single, part, lds, st);
+    else if (len <= 4 * kWG) exact_tile<4>(src, len, m, n, bits, list, count, single, part, lds, st);
+    else if (len <= 10 * kWG) exact_tile<10>(src, len, m, n, bits, list, count, single, part, lds, st);
+    else exact_tile<0>(src, len, m, n, bits, list, count, single, part, lds, st);
+}
+
+constexpr int kListCap = 2048;   // kept candidates of a single-tile group, per round
+
+__global__ __launch_bounds__(kWG) void k_exact(Tables tb, int n, int bits,
                                                const float *__restrict__ gm,
                                                const float *__restrict__ sse32,
-                                               const uint32_t *__restrict__ mask,
+                                               const int *__restrict__ klist,
                                                double *__restrict__ part64,
                                                float *__restrict__ p_star,
                                                float *__restrict__ m_out,
                                                int32_t *__restrict__ k_star,
                                                double *__restrict__ mse)
 {
-    extern __shared__ uint32_t lmask[];          // single-tile groups: ceil(n/256)*8 words
+    __shared__ int llist[kListCap];
+    __shared__ int lcount;
     __shared__ double lds[kWaves * 2];
     const int t = blockIdx.x;
     const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
     TensorRec r;
     TileInfo ti = tile_of(tb, t, r);
     const bool single = r.tpg == 1;
     const float m = gm[ti.group];
     const long long og = r.out_group + ti.group_local;
     const bool usable = (m > 0.0f) && (m < __builtin_inff());
-
-    BitCursor cur;
-    cur.wi = -1;
-    cur.word = 0;
-    if (single) {
-        const int lwords = (n + kWG - 1) / kWG * 8;
-        if (!usable) {
-            for (int wi = tid; wi < lwords; wi += kWG) lmask[wi] = (wi == 0 && m == 0.0f) ? 1u : 0u;
-        } else {
-            const float *row = sse32 + (long long)t * n;
-            double mn = __builtin_inf();
-            for (int k0 = tid; k0 < n; k0 += kWG) mn = fmin(mn, (double)row[k0]);
-            mn = block_min(mn, lds);
-            const double thr = keep_threshold(mn, (double)r.gcount, n);
-            for (int base = 0; base < n; base += kWG) {
-                const int k0 = base + tid;
-                const bool keep = (k0 < n) && ((double)row[k0] <= thr);
-                const unsigned long long bal = __ballot(keep);
-                if (lane == 0) {
-                    lmask[(base >> 5) + wave * 2] = (uint32_t)bal;
-                    lmask[(base >> 5) + wave * 2 + 1] = (uint32_t)(bal >> 32);
-                }
-            }
-        }
-        __syncthreads();
-        cur.words = lmask;
-        cur.nwords = lwords;
-    } else {
-        cur.words = mask + (long long)ti.group * nwords;
-        cur.nwords = nwords;
-    }
-
-    double *part = single ? nullptr
-                          : part64 + (long long)(r.part_base + ti.local_tile) * n;
     ExactState st;
     st.best = 0.0;
     st.best_k = -1;
-    st.slot = 0;
-    if (ti.len <= kWG)
-        exact_tile<1>(ti.src, ti.len, m, n, bits, cur, single, part, lds, st);
-    else if (ti.len <= 4 * kWG)
-        exact_tile<4>(ti.src, ti.len, m, n, bits, cur, single, part, lds, st);
-    else if (ti.len <= 10 * kWG)
-        exact_tile<10>(ti.src, ti.len, m, n, bits, cur, single, part, lds, st);
-    else
-        exact_tile<0>(ti.src, ti.len, m, n, bits, cur, single, part, lds, st);
 
-    if (single && tid == 0) {
+    if (!single) {
+        // the group's list was built by k_flag; sums go to this tile's row
+        const int mg = r.mgroup_base + ti.group_local;
+        const int *list = klist + (long long)mg * (n + 1);
+        const int count = uni(list[0]);
+        double *part = part64 + (long long)(r.part_base + ti.local_tile) * n;
+        exact_dispatch(ti.src, ti.len, m, n, bits, list + 1, count, false, part, lds, st);
+        return;
+    }
+
+    // single-tile group: filter here, a round of at most kListCap candidates at a time
+    if (m == 0.0f) {
+        if (tid == 0) llist[0] = 1;
+        __syncthreads();
+        exact_dispatch(ti.src, ti.len, m, n, bits, llist, 1, true, nullptr, lds, st);
+    } else if (usable) {
+        const float *row = sse32 + (long long)t * n;
+        double mn = __builtin_inf();
+        for (int k0 = tid; k0 < n; k0 += kWG) mn = fmin(mn, (double)row[k0]);
+        mn = block_min(mn, lds);
+        const double thr = keep_threshold(mn, (double)r.gcount, n);
+        for (int rbase = 0; rbase < n; rbase += kListCap) {
+            __syncthreads();
+            if (tid == 0) lcount = 0;
+            __syncthreads();
+            const int rend = (rbase + kListCap < n) ? rbase + kListCap : n;
+            for (int k0 = rbase + tid; k0 < rend; k0 += kWG)
+                if ((double)row[k0] <= thr) llist[atomicAdd(&lcount, 1)] = k0 + 1;
+            __syncthreads();
+            const int count = uni(lcount);
+            exact_dispatch(ti.src, ti.len, m, n, bits, llist, count, true, nullptr, lds, st);
+        }
+    }
+    if (tid == 0) {
         m_out[og] = m;
         if (st.best_k < 0) {
             k_star[og] = -1;
@@ -268,10 +264,10 @@ __global__ __launch_bounds__(kWG) void k_exact(Tables tb, int n, int nwords, int
 
 // ------------------------------------------------------------------- final
 // Groups spread over several tiles: add the tiles' partial sums in tile order,
-// then take the smallest sum, lowest candidate first.
-__global__ __launch_bounds__(kWG) void k_final(Tables tb, int n, int nwords,
+// then take the smallest sum, lowest candidate first (the list is ascending).
+__global__ __launch_bounds__(kWG) void k_final(Tables tb, int n,
                                                const float *__restrict__ gm,
-                                               const uint32_t *__restrict__ mask,
+                                               const int *__restrict__ klist,
                                                const double *__restrict__ part64,
                                                float *__restrict__ p_star,
                                                float *__restrict__ m_out,
@@ -288,14 +284,13 @@ __global__ __launch_bounds__(kWG) void k_final(Tables tb, int n, int nwords,
     const int g = r.group_base + gl;
     const long long og = r.out_group + gl;
     const float m = gm[g];
-    const uint32_t *gmask = mask + (long long)g * nwords;
-    int nflag = 0;
-    for (int wi = 0; wi < nwords; ++wi) nflag += __builtin_popcount(gmask[wi]);
+    const int *list = klist + (long long)mg * (n + 1);
+    const int count = list[0];
     const double *part = part64 + (long long)(r.part_base + gl * r.tpg) * n;
 
     double best = __builtin_inf();
     int best_slot = 0x7fffffff;
-    for (int s = tid; s < nflag; s += kWG) {
+    for (int s = tid; s < count; s += kWG) {
         double v = 0.0;
         for (int j = 0; j < r.tpg; ++j) v += part[(long long)j * n + s];
         if (v < best) { best = v; best_slot = s; }
@@ -313,21 +308,12 @@ __global__ __launch_bounds__(kWG) void k_final(Tables tb, int n, int nwords,
     if (tid == 0) {
         for (int i = 1; i < kWaves; ++i) cand = slot_lds[i] < cand ? slot_lds[i] : cand;
         m_out[og] = m;
-        if (nflag == 0 || cand == 0x7fffffff) {
+        if (count == 0 || cand == 0x7fffffff) {
             k_star[og] = -1;
             p_star[og] = __builtin_nanf("");
             mse[og] = __builtin_nan("");
         } else {
-            int k = -1, seen = 0;
-            for (int wi = 0; wi < nwords && k < 0; ++wi) {
-                uint32_t word = gmask[wi];
-                int c = __builtin_popcount(word);
-                if (seen + c > cand) {
-                    for (int i = 0; i < cand - seen; ++i) word &= word - 1;
-                    k = wi * 32 + __builtin_ctz(word) + 1;
-                }
-                seen += c;
-            }
+            const int k = list[1 + cand];
             k_star[og] = k;
             p_star[og] = grid_point(m, k, n);
             mse[og] = wbest / (double)r.gcount;
