@@ -109,21 +109,27 @@ struct ExactState {
 // the lexicographic (sum, k) minimum, so the order of the list does not matter;
 // tiles of longer groups store the sums in list order.
 template <int kEpt>
-__device__ inline void exact_tile(const float *__restrict__ src, int len, float m, int n, int bits,
+__device__ inline void load_tile(const float *__restrict__ src, int len,
+                                 float (&a)[kEpt > 0 ? kEpt : 1])
+{
+    if (kEpt > 0) {
+#pragma unroll
+        for (int e = 0; e < kEpt; ++e) {
+            const int i = threadIdx.x + e * kWG;
+            a[e] = (i < len) ? fabsf(src[i]) : 0.0f;
+        }
+    }
+}
+
+template <int kEpt>
+__device__ inline void exact_tile(const float *__restrict__ src, int len,
+                                  const float (&a)[kEpt > 0 ? kEpt : 1], float m, int n, int bits,
                                   const int *list, int count, bool single,
                                   double *__restrict__ part, double *lds, ExactState &st)
 {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    float a[kEpt > 0 ? kEpt : 1];
-    if (kEpt > 0) {
-#pragma unroll
-        for (int e = 0; e < kEpt; ++e) {
-            const int i = tid + e * kWG;
-            a[e] = (i < len) ? fabsf(src[i]) : 0.0f;
-        }
-    }
     for (int c = 0; c < count; c += 2) {
         const int k0 = list[c];
         const int k1 = (c + 1 < count) ? list[c + 1] : -1;
@@ -178,17 +184,75 @@ __device__ inline void exact_tile(const float *__restrict__ src, int len, float 
     }
 }
 
-__device__ inline void exact_dispatch(const float *__restrict__ src, int len, float m, int n,
-                                      int bits, const int *list, int count, bool single,
-                                      double *__restrict__ part, double *lds, ExactState &st)
-{
-    if (len <= kWG) exact_tile<1>(src, len, m, n, bits, list, count, single, part, lds, st);
-    else if (len <= 4 * kWG) exact_tile<4>(src, len, m, n, bits, list, count, single, part, lds, st);
-    else if (len <= 10 * kWG) exact_tile<10>(src, len, m, n, bits, list, count, single, part, lds, st);
-    else exact_tile<0>(src, len, m, n, bits, list, count, single, part, lds, st);
-}
-
 constexpr int kListCap = 2048;   // kept candidates of a single-tile group, per round
+
+// The thread's elements are loaded first, so that their memory latency
+// overlaps the filtering that follows.
+template <int kEpt>
+__device__ inline void exact_body(const TensorRec &r, const TileInfo &ti, int t, int n, int bits,
+                                  const float *__restrict__ gm, const float *__restrict__ sse32,
+                                  const int *__restrict__ klist, double *__restrict__ part64,
+                                  float *__restrict__ p_star, float *__restrict__ m_out,
+                                  int32_t *__restrict__ k_star, double *__restrict__ mse,
+                                  int *llist, int *lcount, double *lds)
+{
+    const int tid = threadIdx.x;
+    float a[kEpt > 0 ? kEpt : 1];
+    load_tile<kEpt>(ti.src, ti.len, a);
+    const bool single = r.tpg == 1;
+    const float m = gm[ti.group];
+    const long long og = r.out_group + ti.group_local;
+    const bool usable = (m > 0.0f) && (m < __builtin_inff());
+    ExactState st;
+    st.best = 0.0;
+    st.best_k = -1;
+
+    if (!single) {
+        // the group's list was built by k_flag; sums go to this tile's row
+        const int mg = r.mgroup_base + ti.group_local;
+        const int *list = klist + (long long)mg * (n + 1);
+        const int count = uni(list[0]);
+        double *part = part64 + (long long)(r.part_base + ti.local_tile) * n;
+        exact_tile<kEpt>(ti.src, ti.len, a, m, n, bits, list + 1, count, false, part, lds, st);
+        return;
+    }
+
+    // single-tile group: filter here, a round of at most kListCap candidates at a time
+    if (m == 0.0f) {
+        if (tid == 0) llist[0] = 1;
+        __syncthreads();
+        exact_tile<kEpt>(ti.src, ti.len, a, m, n, bits, llist, 1, true, nullptr, lds, st);
+    } else if (usable) {
+        const float *row = sse32 + (long long)t * n;
+        double mn = __builtin_inf();
+        for (int k0 = tid; k0 < n; k0 += kWG) mn = fmin(mn, (double)row[k0]);
+        mn = block_min(mn, lds);
+        const double thr = keep_threshold(mn, (double)r.gcount, n);
+        for (int rbase = 0; rbase < n; rbase += kListCap) {
+            __syncthreads();
+            if (tid == 0) *lcount = 0;
+            __syncthreads();
+            const int rend = (rbase + kListCap < n) ? rbase + kListCap : n;
+            for (int k0 = rbase + tid; k0 < rend; k0 += kWG)
+                if ((double)row[k0] <= thr) llist[atomicAdd(lcount, 1)] = k0 + 1;
+            __syncthreads();
+            const int count = uni(*lcount);
+            exact_tile<kEpt>(ti.src, ti.len, a, m, n, bits, llist, count, true, nullptr, lds, st);
+        }
+    }
+    if (tid == 0) {
+        m_out[og] = m;
+        if (st.best_k < 0) {
+            k_star[og] = -1;
+            p_star[og] = __builtin_nanf("");
+            mse[og] = __builtin_nan("");
+        } else {
+            k_star[og] = st.best_k;
+            p_star[og] = grid_point(m, st.best_k, n);
+            mse[og] = st.best / (double)r.gcount;
+        }
+    }
+}
 
 __global__ __launch_bounds__(kWG) void k_exact(Tables tb, int n, int bits,
                                                const float *__restrict__ gm,
@@ -204,62 +268,20 @@ __global__ __launch_bounds__(kWG) void k_exact(Tables tb, int n, int bits,
     __shared__ int lcount;
     __shared__ double lds[kWaves * 2];
     const int t = blockIdx.x;
-    const int tid = threadIdx.x;
     TensorRec r;
     TileInfo ti = tile_of(tb, t, r);
-    const bool single = r.tpg == 1;
-    const float m = gm[ti.group];
-    const long long og = r.out_group + ti.group_local;
-    const bool usable = (m > 0.0f) && (m < __builtin_inff());
-    ExactState st;
-    st.best = 0.0;
-    st.best_k = -1;
-
-    if (!single) {
-        // the group's list was built by k_flag; sums go to this tile's row
-        const int mg = r.mgroup_base + ti.group_local;
-        const int *list = klist + (long long)mg * (n + 1);
-        const int count = uni(list[0]);
-        double *part = part64 + (long long)(r.part_base + ti.local_tile) * n;
-        exact_dispatch(ti.src, ti.len, m, n, bits, list + 1, count, false, part, lds, st);
-        return;
-    }
-
-    // single-tile group: filter here, a round of at most kListCap candidates at a time
-    if (m == 0.0f) {
-        if (tid == 0) llist[0] = 1;
-        __syncthreads();
-        exact_dispatch(ti.src, ti.len, m, n, bits, llist, 1, true, nullptr, lds, st);
-    } else if (usable) {
-        const float *row = sse32 + (long long)t * n;
-        double mn = __builtin_inf();
-        for (int k0 = tid; k0 < n; k0 += kWG) mn = fmin(mn, (double)row[k0]);
-        mn = block_min(mn, lds);
-        const double thr = keep_threshold(mn, (double)r.gcount, n);
-        for (int rbase = 0; rbase < n; rbase += kListCap) {
-            __syncthreads();
-            if (tid == 0) lcount = 0;
-            __syncthreads();
-            const int rend = (rbase + kListCap < n) ? rbase + kListCap : n;
-            for (int k0 = rbase + tid; k0 < rend; k0 += kWG)
-                if ((double)row[k0] <= thr) llist[atomicAdd(&lcount, 1)] = k0 + 1;
-            __syncthreads();
-            const int count = uni(lcount);
-            exact_dispatch(ti.src, ti.len, m, n, bits, llist, count, true, nullptr, lds, st);
-        }
-    }
-    if (tid == 0) {
-        m_out[og] = m;
-        if (st.best_k < 0) {
-            k_star[og] = -1;
-            p_star[og] = __builtin_nanf("");
-            mse[og] = __builtin_nan("");
-        } else {
-            k_star[og] = st.best_k;
-            p_star[og] = grid_point(m, st.best_k, n);
-            mse[og] = st.best / (double)r.gcount;
-        }
-    }
+    if (ti.len <= kWG)
+        exact_body<1>(r, ti, t, n, bits, gm, sse32, klist, part64, p_star, m_out, k_star, mse, llist,
+                      &lcount, lds);
+    else if (ti.len <= 4 * kWG)
+        exact_body<4>(r, ti, t, n, bits, gm, sse32, klist, part64, p_star, m_out, k_star, mse, llist,
+                      &lcount, lds);
+    else if (ti.len <= 10 * kWG)
+        exact_body<10>(r, ti, t, n, bits, gm, sse32, klist, part64, p_star, m_out, k_star, mse, llist,
+                       &lcount, lds);
+    else
+        exact_body<0>(r, ti, t, n, bits, gm, sse32, klist, part64, p_star, m_out, k_star, mse, llist,
+                      &lcount, lds);
 }
 
 // ------------------------------------------------------------------- final
