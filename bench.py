@@ -179,11 +179,11 @@ def main() -> int:
         from oracle import pwlq_ref
         pwlq_ref.search(host[0][:2], wl.bits, 8, wl.mode)            # load the library
         if wl.mode == synth.PER_CHANNEL:
-            stride = 2 if wl.n_evals > 4e9 else 1
-            if wl.index == 5:
-                stride = 16
+            # about 2.5e10 evaluations: a few seconds on the host cores of the GPU machine
+            stride = max(1, int(round(wl.n_evals / 2.6e10)))
             sample = [t[::stride] for t in host]
-            what = f"every {stride}th channel of every tensor" if stride > 1 else "whole workload"
+            what = (f"one channel in every {stride} of every tensor" if stride > 1
+                    else "the whole workload")
         else:
             order = np.argsort([t.size for t in host])
             sample = [host[i] for i in order[: len(order) // 2]]

@@ -106,6 +106,29 @@ def test_long_channels_split_into_tiles(P):
     run_both(P, w, 4, 500, synth.PER_CHANNEL, "per-channel K=30011")
 
 
+# ------------------------------------------------- distributions the filter must survive
+@pytest.mark.parametrize("bits", [2, 3, 4, 6, 8])
+def test_many_distributions(P, bits):
+    """The binary32 pass only filters candidates; the kept set must always hold
+    the true argmin.  Mix of shapes that move the optimum around (uniform and
+    bimodal groups put it above m/2, sparse and heavy-tailed ones near 0)."""
+    rng = np.random.default_rng(1000 + bits)
+    rows = []
+    K = 768
+    for _ in range(40):
+        rows.append(rng.uniform(-1, 1, K))
+        rows.append(np.sign(rng.standard_normal(K)) * (0.8 + 0.2 * rng.random(K)))
+        rows.append(rng.standard_normal(K) * (rng.random(K) < 0.05))
+        rows.append(rng.standard_t(1.5, K))
+        rows.append(rng.laplace(0, 1, K) ** 3)
+        rows.append(np.round(rng.standard_normal(K) * 4) / 4)            # few distinct values: exact ties
+        rows.append(rng.standard_normal(K) * np.exp(rng.normal(0, 2)))
+        rows.append(np.concatenate([rng.normal(0, 0.01, K - 8), rng.normal(0, 1, 8)]))
+    w = np.stack(rows).astype(np.float32)
+    run_both(P, w, bits, 333, synth.PER_CHANNEL, f"distributions bits={bits}")
+    run_both(P, w[:64].reshape(8, -1), bits, 257, synth.PER_CHANNEL, f"distributions long bits={bits}")
+
+
 # ------------------------------------------------------------------ degenerate
 def test_degenerate_groups(P):
     w = np.zeros((8, 100), np.float32)
