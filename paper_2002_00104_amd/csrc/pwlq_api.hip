@@ -33,9 +33,9 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // Everything a call needs to know about its tensors, built on the host.
 struct Plan {
     std::vector<TensorRec> recs;
-    std::vector<int> tile_prefix, group_prefix, unit_prefix, mgroup_prefix;
+    std::vector<int> tile_prefix, group_prefix, unit_prefix, mgroup_prefix, emit_prefix;
     int nt = 0;
-    long long n_tiles = 0, n_groups = 0, n_units = 0, n_mgroups = 0, n_part_tiles = 0;
+    long long n_tiles = 0, n_groups = 0, n_units = 0, n_mgroups = 0, n_part_tiles = 0, n_chunks = 0;
     long long sorted_elems = 0;
     int n = 0, nblk = 0, nwords = 0;
     // workspace offsets in bytes
@@ -109,7 +109,8 @@ int build_plan(Plan &pl, const pwlq_tensor_desc *desc, int n_tensors, int n_cand
     pl.group_prefix.assign(n_tensors + 1, 0);
     pl.unit_prefix.assign(n_tensors + 1, 0);
     pl.mgroup_prefix.assign(n_tensors + 1, 0);
-    long long tiles = 0, groups = 0, units = 0, mgroups = 0, parts = 0, sorted = 0;
+    pl.emit_prefix.assign(n_tensors + 1, 0);
+    long long tiles = 0, groups = 0, units = 0, mgroups = 0, parts = 0, sorted = 0, chunks = 0;
     for (int s = 0; s < n_tensors; ++s) {
         TensorRec r = tmp[order[s].idx];
         r.tile_base = (int)tiles;
@@ -122,12 +123,15 @@ int build_plan(Plan &pl, const pwlq_tensor_desc *desc, int n_tensors, int n_cand
         pl.group_prefix[s] = (int)groups;
         pl.unit_prefix[s] = (int)units;
         pl.mgroup_prefix[s] = (int)mgroups;
+        pl.emit_prefix[s] = (int)chunks;
+        r.emit_base = (int)chunks;
+        chunks += ((long long)r.ngroups * r.gcount + kEmitChunk - 1) / kEmitChunk;
         tiles += r.ntiles;
         groups += r.ngroups;
         units += (r.ntiles + r.tpu - 1) / r.tpu;
         if (r.tpg > 1) { mgroups += r.ngroups; parts += r.ntiles; }
         sorted += (long long)r.ntiles * r.stride;
-        if (tiles > 0x3fffffffLL || units > 0x3fffffffLL)
+        if (tiles > 0x3fffffffLL || units > 0x3fffffffLL || chunks > 0x3fffffffLL)
             return fail(PWLQ_EINVAL, "call has too many tiles");
         pl.recs[s] = r;
     }
@@ -135,6 +139,8 @@ int build_plan(Plan &pl, const pwlq_tensor_desc *desc, int n_tensors, int n_cand
     pl.group_prefix[n_tensors] = (int)groups;
     pl.unit_prefix[n_tensors] = (int)units;
     pl.mgroup_prefix[n_tensors] = (int)mgroups;
+    pl.emit_prefix[n_tensors] = (int)chunks;
+    pl.n_chunks = chunks;
     pl.n_tiles = tiles;
     pl.n_groups = groups;
     pl.n_units = units;
@@ -145,7 +151,7 @@ int build_plan(Plan &pl, const pwlq_tensor_desc *desc, int n_tensors, int n_cand
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes, 256); return at; };
     pl.off_recs = take(sizeof(TensorRec) * (size_t)n_tensors);
-    pl.off_prefix = take(sizeof(int) * 4 * (size_t)(n_tensors + 1));
+    pl.off_prefix = take(sizeof(int) * 5 * (size_t)(n_tensors + 1));
     if (n_cand > 0) {
         pl.off_tile_max = take(sizeof(float) * (size_t)tiles);
         pl.off_gm = take(sizeof(float) * (size_t)groups);
@@ -183,11 +189,12 @@ int upload_tables(const Plan &pl, char *ws, hipStream_t stream, Tables &tb)
         return PWLQ_OK;
     }
     std::vector<int> prefix;
-    prefix.reserve(4 * (size_t)(pl.nt + 1));
+    prefix.reserve(5 * (size_t)(pl.nt + 1));
     prefix.insert(prefix.end(), pl.tile_prefix.begin(), pl.tile_prefix.end());
     prefix.insert(prefix.end(), pl.group_prefix.begin(), pl.group_prefix.end());
     prefix.insert(prefix.end(), pl.unit_prefix.begin(), pl.unit_prefix.end());
     prefix.insert(prefix.end(), pl.mgroup_prefix.begin(), pl.mgroup_prefix.end());
+    prefix.insert(prefix.end(), pl.emit_prefix.begin(), pl.emit_prefix.end());
     hipError_t e = hipMemcpyAsync(ws + pl.off_recs, pl.recs.data(),
                                   sizeof(TensorRec) * (size_t)pl.nt, hipMemcpyHostToDevice, stream);
     if (e == hipSuccess)
@@ -200,6 +207,7 @@ int upload_tables(const Plan &pl, char *ws, hipStream_t stream, Tables &tb)
     tb.group_prefix = p + (pl.nt + 1);
     tb.unit_prefix = p + 2 * (pl.nt + 1);
     tb.mgroup_prefix = p + 3 * (pl.nt + 1);
+    tb.emit_prefix = p + 4 * (pl.nt + 1);
     return PWLQ_OK;
 }
 
@@ -313,7 +321,7 @@ int run_quantize(const pwlq_tensor_desc *desc, int n_tensors, int bits, int mode
     rc = upload_tables(pl, (char *)workspace, stream, tb);
     if (rc) return rc;
     profile_mark(2, stream);
-    k_emit<<<(int)pl.n_tiles, kWG, 0, stream>>>(tb, bits, p_star, m, codes, flags, w_hat);
+    k_emit<<<(int)pl.n_chunks, kWG, 0, stream>>>(tb, bits, p_star, m, codes, flags, w_hat);
     profile_mark(3, stream);
     return launch_status("quantize launch");
 }

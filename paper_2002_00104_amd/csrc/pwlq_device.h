@@ -19,6 +19,7 @@ constexpr int kTileMax = 8192;    // longest run of a group handled by one workg
 constexpr int kPerThread = kTileMax / kWG;  // elements of a tile held by one thread
 constexpr int kUnitElems = 4096;  // small tiles are batched up to about this many elements
 constexpr int kMinUnits = 4096;   // ... unless that would leave fewer search units than this
+constexpr int kEmitChunk = 4096;  // elements per workgroup of the quantize kernel
 constexpr int kVec = 8;           // elements per scalar vector load in the search loop
 constexpr int kChunk = 128;       // elements per inner fp32 accumulation chunk
 
@@ -35,6 +36,7 @@ struct TensorRec {
     int tpu;               // tiles per search unit
     int part_base;         // first partial-sum row (multi-tile groups), else -1
     int tile_base, group_base, unit_base, mgroup_base;
+    int emit_base;         // first chunk of this tensor in the quantize kernel's grid
     int ntiles, ngroups;
 };
 

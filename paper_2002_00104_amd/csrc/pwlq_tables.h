@@ -12,7 +12,7 @@ typedef float float8 __attribute__((ext_vector_type(8)));
 // prefix arrays from the head of the workspace.
 struct Tables {
     const TensorRec *recs;
-    const int *tile_prefix, *group_prefix, *unit_prefix, *mgroup_prefix;
+    const int *tile_prefix, *group_prefix, *unit_prefix, *mgroup_prefix, *emit_prefix;
     int nt;
     int n_units;
     TensorRec one;
@@ -46,6 +46,7 @@ __device__ inline TensorRec rec_of(const Tables &tb, int i)
     r.group_base = uni(r.group_base);
     r.unit_base = uni(r.unit_base);
     r.mgroup_base = uni(r.mgroup_base);
+    r.emit_base = uni(r.emit_base);
     r.ntiles = uni(r.ntiles);
     r.ngroups = uni(r.ngroups);
     return r;

@@ -85,7 +85,8 @@ def test_bit_widths(P, bits):
     run_both(P, w, bits, 300, synth.PER_CHANNEL, f"bits={bits}")
 
 
-@pytest.mark.parametrize("n", [1, 2, 7, 63, 64, 65, 128, 129, 1000, 2048, 2049, 5000])
+@pytest.mark.parametrize("n", [1, 2, 7, 63, 64, 65, 128, 129, 1000, 1024, 1025, 2048, 2049, 5000,
+                               65535])
 def test_candidate_counts(P, n):
     rng = np.random.default_rng(n)
     w = rng.laplace(0, 0.05, size=(9, 333)).astype(np.float32)
