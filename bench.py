@@ -57,6 +57,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", type=int, default=2, help="1..5 (default 2: ResNet-50 shapes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only-k", type=int, default=0,
+                    help="keep only the tensors whose rows have this many elements "
+                         "(e.g. 9: the depthwise channels of workload 3)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 256 MiB device copy three times (scales the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run) and exit")
@@ -85,6 +88,11 @@ def main() -> int:
         return 0
     wl = synth.workload(args.workload)
     host = list(wl.tensors())
+    if args.only_k:
+        host = [t for t in host if t.shape[1] == args.only_k]
+        if not host:
+            print(f"workload {wl.index} has no tensor with K={args.only_k}", file=sys.stderr)
+            return 2
     dev = [torch.from_numpy(t).cuda() for t in host]
     tl = pwlq.TensorList(dev, wl.mode)
     ws_search = torch.empty(pwlq.search_list_workspace_bytes(tl, wl.bits, wl.n_cand),
@@ -125,7 +133,8 @@ def main() -> int:
     pwlq.profile_enable(False)
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    evals = wl.n_evals
+    n_elements = sum(t.size for t in host)
+    evals = n_elements * wl.n_cand
     value = evals / (ms_per_step * 1e-3)
     ks = float(np.mean(k_search_ms))
     achieved = LANE_OPS_PER_EVAL * evals / (ks * 1e-3)
@@ -144,8 +153,9 @@ def main() -> int:
         "dtype": "f32",
         "data": "synthetic",
         "config": {
-            "workload": f"configs[{wl.index - 1}] {wl.name}: {wl.n_tensors} tensors, "
-                        f"{wl.n_groups} groups, {wl.n_elements} fp32 weights, "
+            "workload": f"configs[{wl.index - 1}] {wl.name}: {len(host)} tensors, "
+                        f"{tl.n_groups} groups, {n_elements} fp32 weights"
+                        f"{' (only K=%d)' % args.only_k if args.only_k else ''}, "
                         f"{'per-channel' if wl.mode == 0 else 'per-tensor'}, b={wl.bits}, "
                         f"{wl.n_cand} candidates",
             "evals_per_step": evals,
@@ -160,17 +170,17 @@ def main() -> int:
             "peak": PEAK_LANE_OPS / 1e12,
             "unit": "Tlane-op/s (fp32 VALU lane-instructions; 9 per evaluation, algorithmic)",
             "frac": achieved / PEAK_LANE_OPS,
-            "traffic": _measured_traffic(wl.index, pwlq.kernel_name(0)),
+            "traffic": None if args.only_k else _measured_traffic(wl.index, pwlq.kernel_name(0)),
             "kernel_ms": ks,
             "kernel_evals_per_s": evals / (ks * 1e-3),
         },
         "quantize_roofline": {
             "kernel": pwlq.kernel_name(1),
             "bound": "hbm",
-            "achieved": 10.0 * wl.n_elements / (emit_ms * 1e-3) / 1e9,
+            "achieved": 10.0 * n_elements / (emit_ms * 1e-3) / 1e9,
             "peak": 8000.0,
             "unit": "GB/s",
-            "frac": 10.0 * wl.n_elements / (emit_ms * 1e-3) / 8e12,
+            "frac": 10.0 * n_elements / (emit_ms * 1e-3) / 8e12,
             "kernel_ms": emit_ms,
         },
     }
@@ -180,7 +190,7 @@ def main() -> int:
         pwlq_ref.search(host[0][:2], wl.bits, 8, wl.mode)            # load the library
         if wl.mode == synth.PER_CHANNEL:
             # about 2.5e10 evaluations: a few seconds on the host cores of the GPU machine
-            stride = max(1, int(round(wl.n_evals / 2.6e10)))
+            stride = max(1, int(round(evals / 2.6e10)))
             sample = [t[::stride] for t in host]
             what = (f"one channel in every {stride} of every tensor" if stride > 1
                     else "the whole workload")
