@@ -241,6 +241,50 @@ int pwlq_ref_quantize(const float *w, int64_t C, int64_t K, int bits, int mode,
     return REF_OK;
 }
 
+/*
+ * Storage format of Section 4 ("at most one extra bit per weight"): the b-bit
+ * codes of a tensor as one little-endian bit stream, code i in bits
+ * [i*b, (i+1)*b) counted from bit 0 of byte 0, and the region flags as a second
+ * stream with flag i in bit i.  Unused bits of the last byte are 0.
+ * packed_codes holds ceil(count*bits/8) bytes, packed_flags ceil(count/8).
+ */
+int pwlq_ref_pack(const uint8_t *codes, const uint8_t *flags, int64_t count, int bits,
+                  uint8_t *packed_codes, uint8_t *packed_flags)
+{
+    if (!codes || !flags || !packed_codes || !packed_flags) return REF_ENULL;
+    if (count < 0 || bits < 2 || bits > 8) return REF_EINVAL;
+    int64_t code_bytes = (count * bits + 7) / 8, flag_bytes = (count + 7) / 8;
+    for (int64_t i = 0; i < code_bytes; ++i) packed_codes[i] = 0;
+    for (int64_t i = 0; i < flag_bytes; ++i) packed_flags[i] = 0;
+    for (int64_t i = 0; i < count; ++i) {
+        for (int bit = 0; bit < bits; ++bit) {
+            if ((codes[i] >> bit) & 1) {
+                int64_t pos = i * bits + bit;
+                packed_codes[pos / 8] |= (uint8_t)(1u << (pos % 8));
+            }
+        }
+        if (flags[i] & 1) packed_flags[i / 8] |= (uint8_t)(1u << (i % 8));
+    }
+    return REF_OK;
+}
+
+int pwlq_ref_unpack(const uint8_t *packed_codes, const uint8_t *packed_flags, int64_t count,
+                    int bits, uint8_t *codes, uint8_t *flags)
+{
+    if (!codes || !flags || !packed_codes || !packed_flags) return REF_ENULL;
+    if (count < 0 || bits < 2 || bits > 8) return REF_EINVAL;
+    for (int64_t i = 0; i < count; ++i) {
+        unsigned v = 0;
+        for (int bit = 0; bit < bits; ++bit) {
+            int64_t pos = i * bits + bit;
+            v |= (unsigned)((packed_codes[pos / 8] >> (pos % 8)) & 1) << bit;
+        }
+        codes[i] = (uint8_t)v;
+        flags[i] = (uint8_t)((packed_flags[i / 8] >> (i % 8)) & 1);
+    }
+    return REF_OK;
+}
+
 int pwlq_ref_num_threads(void)
 {
 #ifdef _OPENMP

@@ -51,6 +51,10 @@ def lib() -> ctypes.CDLL:
         L.pwlq_ref_quantize.argtypes = [fp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
                                         ctypes.c_int, fp, fp, bp, bp, fp]
         L.pwlq_ref_num_threads.restype = ctypes.c_int
+        L.pwlq_ref_pack.restype = ctypes.c_int
+        L.pwlq_ref_pack.argtypes = [bp, bp, ctypes.c_int64, ctypes.c_int, bp, bp]
+        L.pwlq_ref_unpack.restype = ctypes.c_int
+        L.pwlq_ref_unpack.argtypes = [bp, bp, ctypes.c_int64, ctypes.c_int, bp, bp]
         _lib = L
     return _lib
 
@@ -110,3 +114,30 @@ def quantize(w: np.ndarray, bits: int, p_star: np.ndarray, m: np.ndarray,
     if rc != 0:
         raise ValueError(f"pwlq_ref_quantize status {rc}")
     return codes, flags, w_hat
+
+
+def pack(codes: np.ndarray, flags: np.ndarray, bits: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Bit-packs a tensor's codes and flags (any shape, row-major order)."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8).reshape(-1)
+    flags = np.ascontiguousarray(flags, dtype=np.uint8).reshape(-1)
+    n = codes.size
+    pc = np.empty((n * bits + 7) // 8, np.uint8)
+    pf = np.empty((n + 7) // 8, np.uint8)
+    rc = lib().pwlq_ref_pack(_ptr(codes, ctypes.c_uint8), _ptr(flags, ctypes.c_uint8), n, bits,
+                             _ptr(pc, ctypes.c_uint8), _ptr(pf, ctypes.c_uint8))
+    if rc != 0:
+        raise ValueError(f"pwlq_ref_pack status {rc}")
+    return pc, pf
+
+
+def unpack(packed_codes: np.ndarray, packed_flags: np.ndarray, count: int,
+           bits: int) -> Tuple[np.ndarray, np.ndarray]:
+    pc = np.ascontiguousarray(packed_codes, dtype=np.uint8)
+    pf = np.ascontiguousarray(packed_flags, dtype=np.uint8)
+    codes = np.empty(count, np.uint8)
+    flags = np.empty(count, np.uint8)
+    rc = lib().pwlq_ref_unpack(_ptr(pc, ctypes.c_uint8), _ptr(pf, ctypes.c_uint8), count, bits,
+                               _ptr(codes, ctypes.c_uint8), _ptr(flags, ctypes.c_uint8))
+    if rc != 0:
+        raise ValueError(f"pwlq_ref_unpack status {rc}")
+    return codes, flags

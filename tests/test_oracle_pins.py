@@ -403,3 +403,40 @@ def test_argument_checks():
         kw.update(bad)
         with pytest.raises(ValueError):
             R.search(w, kw["bits"], kw["n_cand"])
+
+
+# ------------------------------------------------------------ packed storage
+def test_packed_format_hand_examples():
+    cases = {}
+    with open(os.path.join(GOLD, "packed_example.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            left, right = line.split("|")
+            name, bits, *vals = left.split()
+            cases[name] = (int(bits), [int(v) for v in vals], bytes.fromhex("".join(right.split())))
+    for name in ("A", "B"):
+        bits, vals, want = cases[name]
+        pc, _ = R.pack(np.array(vals, np.uint8), np.zeros(len(vals), np.uint8), bits)
+        assert pc.tobytes() == want, name
+    _, vals, want = cases["C"]
+    _, pf = R.pack(np.zeros(len(vals), np.uint8), np.array(vals, np.uint8), 4)
+    assert pf.tobytes() == want
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4, 5, 6, 7, 8])
+def test_packed_round_trip_and_sizes(bits):
+    rng = np.random.default_rng(bits)
+    for count in (0, 1, 7, 8, 9, 1000, 4099):
+        codes = rng.integers(0, 1 << bits, size=count).astype(np.uint8)
+        flags = rng.integers(0, 2, size=count).astype(np.uint8)
+        pc, pf = R.pack(codes, flags, bits)
+        assert pc.size == (count * bits + 7) // 8 and pf.size == (count + 7) // 8
+        c2, f2 = R.unpack(pc, pf, count, bits)
+        np.testing.assert_array_equal(c2, codes)
+        np.testing.assert_array_equal(f2, flags)
+        # independent statement of the layout with numpy's bit order
+        want = np.packbits(((codes[:, None] >> np.arange(bits)) & 1).astype(np.uint8).reshape(-1),
+                           bitorder="little")
+        np.testing.assert_array_equal(pc, want)
+        np.testing.assert_array_equal(pf, np.packbits(flags, bitorder="little"))
