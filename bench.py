@@ -185,6 +185,33 @@ def main() -> int:
         },
     }
 
+    # Bit-packed quantizer output (b-bit code stream + 1-bit flag stream, no
+    # dequantized copy): not part of the step above, timed on its own.
+    layout = pwlq.PackedLayout(tl, wl.bits)
+    pout = (torch.empty(max(layout.code_bytes, 4), dtype=torch.uint8, device="cuda"),
+            torch.empty(max(layout.flag_bytes, 4), dtype=torch.uint8, device="cuda"), None)
+    for _ in range(2):
+        pwlq.quantize_packed_list(tl, wl.bits, out["p_star"], out["m"], layout=layout,
+                                  workspace=ws_quant, out=pout)
+    torch.cuda.synchronize()
+    reps = max(3, min(args.steps, 10))
+    e0.record()
+    for _ in range(reps):
+        pwlq.quantize_packed_list(tl, wl.bits, out["p_star"], out["m"], layout=layout,
+                                  workspace=ws_quant, out=pout)
+    e1.record()
+    e1.synchronize()
+    packed_ms = e0.elapsed_time(e1) / reps
+    packed_bytes = n_elements * (4.0 + wl.bits / 8.0 + 1.0 / 8.0)
+    result["quantize_packed"] = {
+        "ms": packed_ms,
+        "bytes_per_element": 4.0 + wl.bits / 8.0 + 1.0 / 8.0,
+        "achieved": packed_bytes / (packed_ms * 1e-3) / 1e9,
+        "peak": 8000.0,
+        "unit": "GB/s",
+        "note": "call time (table upload + kernel), w_hat not requested",
+    }
+
     if not args.no_cpu_baseline:
         from oracle import pwlq_ref
         pwlq_ref.search(host[0][:2], wl.bits, 8, wl.mode)            # load the library

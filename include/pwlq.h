@@ -110,6 +110,36 @@ int pwlq_quantize_list(const pwlq_tensor_desc *desc, int n_tensors, int bits, in
                        const float *p_star, const float *m, uint8_t *codes, uint8_t *flags,
                        float *w_hat, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Quantizer with bit-packed outputs: the storage format Section 4 argues for
+ * (b bits per weight plus one region bit).  Same arithmetic as pwlq_quantize;
+ * only the layout of codes and flags differs:
+ *   packed_codes  one little-endian bit stream per tensor: the b-bit code of
+ *                 row-major element i occupies stream bits [i*b, (i+1)*b),
+ *                 where stream bit j is bit (j mod 8) of byte (j div 8);
+ *                 pwlq_packed_code_bytes(C*K, bits) = ceil(C*K*b/8) bytes
+ *   packed_flags  region flag of element i in stream bit i;
+ *                 pwlq_packed_flag_bytes(C*K) = ceil(C*K/8) bytes
+ *   w_hat         as in pwlq_quantize, or NULL to skip it
+ * Unused bits of a stream's last byte are written as 0.  In the list variant
+ * tensor t's streams start at packed_codes + code_byte_offset[t] and
+ * packed_flags + flag_byte_offset[t] (host arrays of n_tensors entries chosen
+ * by the caller so that streams do not overlap); w_hat, if given, is indexed by
+ * the descriptors' elem_offset.  Workspace: as pwlq_quantize_list.
+ */
+size_t pwlq_packed_code_bytes(int64_t count, int bits);
+size_t pwlq_packed_flag_bytes(int64_t count);
+
+int pwlq_quantize_packed(const float *w, int64_t C, int64_t K, int bits, int mode,
+                         const float *p_star, const float *m, uint8_t *packed_codes,
+                         uint8_t *packed_flags, float *w_hat, void *stream);
+
+int pwlq_quantize_packed_list(const pwlq_tensor_desc *desc, int n_tensors, int bits, int mode,
+                              const float *p_star, const float *m, uint8_t *packed_codes,
+                              const int64_t *code_byte_offset, uint8_t *packed_flags,
+                              const int64_t *flag_byte_offset, float *w_hat, void *workspace,
+                              size_t workspace_bytes, void *stream);
+
 /* Text of the calling thread's last non-OK status ("" if none).  The storage
  * is thread-local and owned by the library. */
 const char *pwlq_last_error(void);

@@ -53,7 +53,8 @@ int check_common(int bits, int mode)
 
 // n_cand == 0 builds a quantize-only plan (no search scratch).
 int build_plan(Plan &pl, const pwlq_tensor_desc *desc, int n_tensors, int n_cand, int mode,
-               bool need_pointers)
+               bool need_pointers, const int64_t *code_byte_offset = nullptr,
+               const int64_t *flag_byte_offset = nullptr)
 {
     if (!desc) return fail(PWLQ_ENULL, "tensor descriptor table is NULL");
     if (n_tensors < 1) return fail(PWLQ_EINVAL, "n_tensors=%d must be >= 1", n_tensors);
@@ -80,6 +81,10 @@ int build_plan(Plan &pl, const pwlq_tensor_desc *desc, int n_tensors, int n_cand
         r.gcount = (mode == PWLQ_PER_CHANNEL) ? d.K : d.C * d.K;
         r.out_elem = d.elem_offset;
         r.out_group = d.group_offset;
+        r.out_code_byte = code_byte_offset ? code_byte_offset[i] : 0;
+        r.out_flag_byte = flag_byte_offset ? flag_byte_offset[i] : 0;
+        if (r.out_code_byte < 0 || r.out_flag_byte < 0)
+            return fail(PWLQ_EINVAL, "desc[%d]: negative byte offset", i);
         const long long tpg = (r.gcount + kTileMax - 1) / kTileMax;
         r.tile_len = (tpg == 1) ? (int)r.gcount : kTileMax;
         r.last_len = (int)(r.gcount - (tpg - 1) * (long long)r.tile_len);
@@ -326,6 +331,34 @@ int run_quantize(const pwlq_tensor_desc *desc, int n_tensors, int bits, int mode
     return launch_status("quantize launch");
 }
 
+int run_quantize_packed(const pwlq_tensor_desc *desc, int n_tensors, int bits, int mode,
+                        const float *p_star, const float *m, uint8_t *packed_codes,
+                        const int64_t *code_byte_offset, uint8_t *packed_flags,
+                        const int64_t *flag_byte_offset, float *w_hat, void *workspace,
+                        size_t workspace_bytes, void *stream_v)
+{
+    int rc = check_common(bits, mode);
+    if (rc) return rc;
+    if (!p_star || !m || !packed_codes || !packed_flags)
+        return fail(PWLQ_ENULL, "an input or output pointer is NULL");
+    if (n_tensors > 1 && (!code_byte_offset || !flag_byte_offset))
+        return fail(PWLQ_ENULL, "byte offset tables are NULL");
+    Plan pl;
+    rc = build_plan(pl, desc, n_tensors, 0, mode, true, code_byte_offset, flag_byte_offset);
+    if (rc) return rc;
+    if (pl.nt > 1) {
+        rc = check_workspace(pl, workspace, workspace_bytes);
+        if (rc) return rc;
+    }
+    hipStream_t stream = (hipStream_t)stream_v;
+    Tables tb;
+    rc = upload_tables(pl, (char *)workspace, stream, tb);
+    if (rc) return rc;
+    k_emit_packed<<<(int)pl.n_chunks, kWG, 0, stream>>>(tb, bits, p_star, m, packed_codes,
+                                                        packed_flags, w_hat);
+    return launch_status("packed quantize launch");
+}
+
 } // namespace
 
 extern "C" {
@@ -386,6 +419,35 @@ int pwlq_quantize(const float *w, int64_t C, int64_t K, int bits, int mode, cons
     if (!w) return fail(PWLQ_ENULL, "w is NULL");
     pwlq_tensor_desc d = {w, C, K, 0, 0};
     return run_quantize(&d, 1, bits, mode, p_star, m, codes, flags, w_hat, nullptr, 0, stream);
+}
+
+size_t pwlq_packed_code_bytes(int64_t count, int bits)
+{
+    if (count < 0 || bits < 2 || bits > 8) return 0;
+    return (size_t)((count * bits + 7) / 8);
+}
+
+size_t pwlq_packed_flag_bytes(int64_t count) { return count < 0 ? 0 : (size_t)((count + 7) / 8); }
+
+int pwlq_quantize_packed(const float *w, int64_t C, int64_t K, int bits, int mode,
+                         const float *p_star, const float *m, uint8_t *packed_codes,
+                         uint8_t *packed_flags, float *w_hat, void *stream)
+{
+    if (!w) return fail(PWLQ_ENULL, "w is NULL");
+    pwlq_tensor_desc d = {w, C, K, 0, 0};
+    return run_quantize_packed(&d, 1, bits, mode, p_star, m, packed_codes, nullptr, packed_flags,
+                               nullptr, w_hat, nullptr, 0, stream);
+}
+
+int pwlq_quantize_packed_list(const pwlq_tensor_desc *desc, int n_tensors, int bits, int mode,
+                              const float *p_star, const float *m, uint8_t *packed_codes,
+                              const int64_t *code_byte_offset, uint8_t *packed_flags,
+                              const int64_t *flag_byte_offset, float *w_hat, void *workspace,
+                              size_t workspace_bytes, void *stream)
+{
+    return run_quantize_packed(desc, n_tensors, bits, mode, p_star, m, packed_codes,
+                               code_byte_offset, packed_flags, flag_byte_offset, w_hat, workspace,
+                               workspace_bytes, stream);
 }
 
 const char *pwlq_last_error(void) { return g_error; }

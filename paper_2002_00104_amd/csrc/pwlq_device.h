@@ -29,6 +29,7 @@ struct TensorRec {
     long long sorted_base; // first element of this tensor's region in the sorted array
     long long out_elem;    // caller's elem_offset
     long long out_group;   // caller's group_offset
+    long long out_code_byte, out_flag_byte;   // packed quantizer: start of this tensor's streams
     int tile_len;          // full tile length
     int last_len;          // length of the last tile of a group
     int tpg;               // tiles per group

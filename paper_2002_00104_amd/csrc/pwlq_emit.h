@@ -118,4 +118,104 @@ __global__ __launch_bounds__(kWG) void k_emit(Tables tb, int bits,
     }
 }
 
+// Bit-packed variant: a thread takes 8 consecutive elements, i.e. exactly
+// `bits` bytes of the code stream and one byte of the flag stream.  The
+// workgroup assembles its 256*bits code bytes and 256 flag bytes in LDS and
+// writes them out as whole words; w_hat is optional.
+constexpr int kPackPass = 8 * kWG;      // elements per pass of a workgroup
+
+__global__ __launch_bounds__(kWG) void k_emit_packed(Tables tb, int bits,
+                                                     const float *__restrict__ p_star,
+                                                     const float *__restrict__ m_in,
+                                                     uint8_t *__restrict__ packed_codes,
+                                                     uint8_t *__restrict__ packed_flags,
+                                                     float *__restrict__ w_hat)
+{
+    __shared__ uint32_t code_stage[kWG * 8 / 4];
+    __shared__ uint32_t flag_stage[kWG / 4];
+    uint8_t *code_bytes = reinterpret_cast<uint8_t *>(code_stage);
+    uint8_t *flag_bytes = reinterpret_cast<uint8_t *>(flag_stage);
+    const int tid = threadIdx.x;
+    const int chunk = blockIdx.x;
+    const int tensor = find_tensor(tb.emit_prefix, tb.nt, chunk);
+    const TensorRec r = rec_of(tb, tensor);
+    const long long total = (long long)r.ngroups * r.gcount;
+    const float *src = r.w;
+    uint8_t *co = packed_codes + r.out_code_byte;
+    uint8_t *fo = packed_flags + r.out_flag_byte;
+    float *ho = w_hat ? w_hat + r.out_elem : nullptr;
+    const bool small = total < 0x7fffffffLL;
+    const bool in_aligned = (((uintptr_t)src) & 15) == 0;
+    const bool hat_aligned = ho && (((uintptr_t)ho) & 15) == 0;
+    const bool words_ok = ((((uintptr_t)co) | ((uintptr_t)fo)) & 3) == 0;
+
+    for (int pass = 0; pass < kEmitChunk / kPackPass; ++pass) {
+        const long long base = (long long)(chunk - r.emit_base) * kEmitChunk + (long long)pass * kPackPass;
+        if (base >= total) break;
+        const long long e = base + 8LL * tid;
+        float wv[8];
+        if (in_aligned && e + 7 < total) {
+            const float4 a = *reinterpret_cast<const float4 *>(src + e);
+            const float4 b = *reinterpret_cast<const float4 *>(src + e + 4);
+            wv[0] = a.x; wv[1] = a.y; wv[2] = a.z; wv[3] = a.w;
+            wv[4] = b.x; wv[5] = b.y; wv[6] = b.z; wv[7] = b.w;
+        } else {
+#pragma unroll
+            for (int x = 0; x < 8; ++x) wv[x] = (e + x < total) ? src[e + x] : 0.0f;
+        }
+        unsigned long long word = 0;
+        unsigned fbyte = 0;
+        float hv[8];
+        if (e < total) {
+            const long long g = group_of(e, r.gcount, small);
+            const bool one_group = (e - g * r.gcount) + 7 < r.gcount;
+            Pieces q = group_pieces(p_star, m_in, r.out_group + g, bits);
+#pragma unroll
+            for (int x = 0; x < 8; ++x) {
+                if (e + x < total) {
+                    if (!one_group)
+                        q = group_pieces(p_star, m_in,
+                                         r.out_group + group_of(e + x, r.gcount, small), bits);
+                    uint8_t c, f;
+                    emit_one(q, bits, wv[x], c, f, hv[x]);
+                    word |= (unsigned long long)c << (x * bits);
+                    fbyte |= (unsigned)f << x;
+                }
+            }
+        }
+        for (int x = 0; x < bits; ++x) code_bytes[tid * bits + x] = (uint8_t)(word >> (8 * x));
+        flag_bytes[tid] = (uint8_t)fbyte;
+        if (ho && e < total) {
+            if (hat_aligned && e + 7 < total) {
+                *reinterpret_cast<float4 *>(ho + e) = make_float4(hv[0], hv[1], hv[2], hv[3]);
+                *reinterpret_cast<float4 *>(ho + e + 4) = make_float4(hv[4], hv[5], hv[6], hv[7]);
+            } else {
+#pragma unroll
+                for (int x = 0; x < 8; ++x)
+                    if (e + x < total) ho[e + x] = hv[x];
+            }
+        }
+        __syncthreads();
+        // bytes of this pass that exist in the streams
+        long long left = total - base;
+        if (left > kPackPass) left = kPackPass;
+        const int nflag = (int)((left + 7) / 8);
+        const int ncode = (int)((left * bits + 7) / 8);
+        const long long code_at = base / 8 * bits;
+        const long long flag_at = base / 8;
+        if (words_ok) {
+            for (int i = tid; i < ncode / 4; i += kWG)
+                reinterpret_cast<uint32_t *>(co + code_at)[i] = code_stage[i];
+            for (int i = (ncode & ~3) + tid; i < ncode; i += kWG) co[code_at + i] = code_bytes[i];
+            for (int i = tid; i < nflag / 4; i += kWG)
+                reinterpret_cast<uint32_t *>(fo + flag_at)[i] = flag_stage[i];
+            for (int i = (nflag & ~3) + tid; i < nflag; i += kWG) fo[flag_at + i] = flag_bytes[i];
+        } else {
+            for (int i = tid; i < ncode; i += kWG) co[code_at + i] = code_bytes[i];
+            for (int i = tid; i < nflag; i += kWG) fo[flag_at + i] = flag_bytes[i];
+        }
+        __syncthreads();
+    }
+}
+
 } // namespace pwlq

@@ -36,6 +36,8 @@ __device__ inline TensorRec rec_of(const Tables &tb, int i)
     r.sorted_base = uni(r.sorted_base);
     r.out_elem = uni(r.out_elem);
     r.out_group = uni(r.out_group);
+    r.out_code_byte = uni(r.out_code_byte);
+    r.out_flag_byte = uni(r.out_flag_byte);
     r.tile_len = uni(r.tile_len);
     r.last_len = uni(r.last_len);
     r.tpg = uni(r.tpg);

@@ -23,6 +23,8 @@ EXPORTS = (
     "pwlq_search_workspace_bytes", "pwlq_search", "pwlq_quantize",
     "pwlq_search_list_workspace_bytes", "pwlq_search_list",
     "pwlq_quantize_list_workspace_bytes", "pwlq_quantize_list",
+    "pwlq_packed_code_bytes", "pwlq_packed_flag_bytes", "pwlq_quantize_packed",
+    "pwlq_quantize_packed_list",
     "pwlq_last_error", "pwlq_last_search_shape", "pwlq_profile_enable",
     "pwlq_profile_last_ms", "pwlq_kernel_name",
 )
@@ -61,6 +63,15 @@ def _load() -> ctypes.CDLL:
     lib.pwlq_quantize_list_workspace_bytes.argtypes = [dp, ci, ci, ci]
     lib.pwlq_quantize_list.restype = ci
     lib.pwlq_quantize_list.argtypes = [dp, ci, ci, ci, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.pwlq_packed_code_bytes.restype = sz
+    lib.pwlq_packed_code_bytes.argtypes = [i64, ci]
+    lib.pwlq_packed_flag_bytes.restype = sz
+    lib.pwlq_packed_flag_bytes.argtypes = [i64]
+    lib.pwlq_quantize_packed.restype = ci
+    lib.pwlq_quantize_packed.argtypes = [vp, i64, i64, ci, ci, vp, vp, vp, vp, vp, vp]
+    lib.pwlq_quantize_packed_list.restype = ci
+    lib.pwlq_quantize_packed_list.argtypes = [dp, ci, ci, ci, vp, vp, vp, ctypes.POINTER(i64), vp,
+                                              ctypes.POINTER(i64), vp, vp, sz, vp]
     lib.pwlq_last_error.restype = ctypes.c_char_p
     lib.pwlq_last_error.argtypes = []
     lib.pwlq_last_search_shape.restype = None
@@ -211,6 +222,69 @@ def quantize_list(tl: TensorList, bits: int, p_star: torch.Tensor, m: torch.Tens
                                   codes.data_ptr(), flags.data_ptr(), w_hat.data_ptr(),
                                   workspace.data_ptr(), workspace.numel(), _stream()))
     return codes, flags, w_hat
+
+
+def packed_code_bytes(count: int, bits: int) -> int:
+    return int(lib.pwlq_packed_code_bytes(count, bits))
+
+
+def packed_flag_bytes(count: int) -> int:
+    return int(lib.pwlq_packed_flag_bytes(count))
+
+
+def quantize_packed(w: torch.Tensor, bits: int, p_star: torch.Tensor, m: torch.Tensor,
+                    mode: int = PER_CHANNEL, want_w_hat: bool = True):
+    """pwlq_quantize_packed on one [C, K] tensor.
+    Returns (packed_codes u8, packed_flags u8, w_hat f32 or None)."""
+    w = _dev32(w)
+    C, K = w.shape
+    n = C * K
+    pc = torch.empty(packed_code_bytes(n, bits), dtype=torch.uint8, device=w.device)
+    pf = torch.empty(packed_flag_bytes(n), dtype=torch.uint8, device=w.device)
+    w_hat = torch.empty((C, K), dtype=torch.float32, device=w.device) if want_w_hat else None
+    _check(lib.pwlq_quantize_packed(w.data_ptr(), C, K, bits, mode, p_star.data_ptr(),
+                                    m.data_ptr(), pc.data_ptr(), pf.data_ptr(),
+                                    w_hat.data_ptr() if want_w_hat else None, _stream()))
+    return pc, pf, w_hat
+
+
+class PackedLayout:
+    """Byte offsets of every tensor's code and flag stream inside two shared
+    buffers; each stream starts on a 4-byte boundary."""
+
+    def __init__(self, tl: "TensorList", bits: int):
+        n = len(tl)
+        self.code_off = (ctypes.c_int64 * n)()
+        self.flag_off = (ctypes.c_int64 * n)()
+        c = f = 0
+        for i, t in enumerate(tl.tensors):
+            self.code_off[i] = c
+            self.flag_off[i] = f
+            c += (packed_code_bytes(t.numel(), bits) + 3) // 4 * 4
+            f += (packed_flag_bytes(t.numel()) + 3) // 4 * 4
+        self.code_bytes = c
+        self.flag_bytes = f
+
+
+def quantize_packed_list(tl: "TensorList", bits: int, p_star: torch.Tensor, m: torch.Tensor,
+                         layout: Optional[PackedLayout] = None, want_w_hat: bool = False,
+                         workspace: Optional[torch.Tensor] = None, out=None):
+    if layout is None:
+        layout = PackedLayout(tl, bits)
+    if workspace is None:
+        workspace = _workspace(quantize_list_workspace_bytes(tl, bits), tl.device)
+    if out is None:
+        out = (torch.empty(max(layout.code_bytes, 4), dtype=torch.uint8, device=tl.device),
+               torch.empty(max(layout.flag_bytes, 4), dtype=torch.uint8, device=tl.device),
+               torch.empty(tl.n_elements, dtype=torch.float32, device=tl.device)
+               if want_w_hat else None)
+    pc, pf, w_hat = out
+    _check(lib.pwlq_quantize_packed_list(tl.desc, len(tl), bits, tl.mode, p_star.data_ptr(),
+                                         m.data_ptr(), pc.data_ptr(), layout.code_off,
+                                         pf.data_ptr(), layout.flag_off,
+                                         w_hat.data_ptr() if w_hat is not None else None,
+                                         workspace.data_ptr(), workspace.numel(), _stream()))
+    return pc, pf, w_hat, layout
 
 
 def profile_enable(on: bool) -> None:
