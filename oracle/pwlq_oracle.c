@@ -285,6 +285,107 @@ int pwlq_ref_unpack(const uint8_t *packed_codes, const uint8_t *packed_flags, in
     return REF_OK;
 }
 
+/*
+ * The paper's own breakpoint selectors (Section 3.3 and Section 5.1).  They
+ * assume the group follows a zero-mean Gaussian or Laplacian restricted to
+ * [-m, m] and minimise the expected error of Eq.6; the minimiser satisfies the
+ * stationarity condition of Eq.11,
+ *     2 m F(p) = 2 m - p + m (m - 2 p) f(p),   0 < p < m/2,
+ * with F, f the CDF and PDF on the bounded domain (F(-m) = 0, F(m) = 1).
+ * selector 0: Section 5.1's closed form for a Gaussian, read with breakpoint
+ *             and range in units of the standard deviation:
+ *             p = sigma * ln(0.8614 m/sigma + 0.6079);
+ * selector 1: Eq.11 solved for the truncated Gaussian;
+ * selector 2: Eq.11 solved for the truncated Laplacian.
+ * The scale is estimated about zero: sigma^2 = mean(w^2), beta = mean|w|.
+ * All arithmetic in binary64; p is returned rounded to binary32.
+ */
+static double gauss_cdf(double x) { return 0.5 * erfc(-x * 0.70710678118654752440); }
+
+/* Derivative of Eq.6 in p without its factor 2 C(b-1) (Eq.8):
+ * p - 2m + 2m F(p) + m (2p - m) f(p); its root is Eq.11. */
+static double stationarity(double p, double m, double scale, int laplace)
+{
+    double F, f;
+    if (laplace) {
+        double z = 1.0 - exp(-m / scale);           /* mass of |r| <= m          */
+        F = 0.5 + 0.5 * (1.0 - exp(-p / scale)) / z; /* p > 0                     */
+        f = exp(-p / scale) / (2.0 * scale) / z;
+    } else {
+        double z = 2.0 * gauss_cdf(m / scale) - 1.0;
+        F = (gauss_cdf(p / scale) - gauss_cdf(-m / scale)) / z;
+        f = exp(-0.5 * (p / scale) * (p / scale)) / (scale * 2.50662827463100050242) / z;
+    }
+    return p - 2.0 * m + 2.0 * m * F + m * (2.0 * p - m) * f;
+}
+
+static double solve_breakpoint(double m, double scale, int laplace)
+{
+    /* the expected error is convex on (0, m/2) (Lemma 1): bisection on its derivative */
+    double lo = 0.0, hi = 0.5 * m;
+    if (stationarity(hi, m, scale, laplace) <= 0.0) return hi;
+    for (int it = 0; it < 200; ++it) {
+        double mid = 0.5 * (lo + hi);
+        if (stationarity(mid, m, scale, laplace) > 0.0) hi = mid; else lo = mid;
+    }
+    return 0.5 * (lo + hi);
+}
+
+int pwlq_ref_select_analytic(const float *w, int64_t C, int64_t K, int mode, int selector,
+                             float *p_out, float *m_out)
+{
+    if (!w || !p_out || !m_out) return REF_ENULL;
+    if (C < 1 || K < 1 || selector < 0 || selector > 2) return REF_EINVAL;
+    if (mode != REF_PER_CHANNEL && mode != REF_PER_TENSOR) return REF_EINVAL;
+    int64_t G = (mode == REF_PER_CHANNEL) ? C : 1;
+    int64_t count = (mode == REF_PER_CHANNEL) ? K : C * K;
+    for (int64_t g = 0; g < G; ++g) {
+        const float *x = w + g * count;
+        float m = group_absmax(x, count);
+        m_out[g] = m;
+        if (!isfinite(m)) { p_out[g] = NAN; continue; }
+        if (m == 0.0f) { p_out[g] = 0.0f; continue; }
+        double s2 = 0.0, s1 = 0.0;
+        for (int64_t i = 0; i < count; ++i) {
+            double v = (double)x[i];
+            s2 += v * v;
+            s1 += fabs(v);
+        }
+        double sigma = sqrt(s2 / (double)count), beta = s1 / (double)count;
+        double p;
+        if (selector == 0) p = sigma * log(0.8614 * ((double)m / sigma) + 0.6079);
+        else if (selector == 1) p = solve_breakpoint((double)m, sigma, 0);
+        else p = solve_breakpoint((double)m, beta, 1);
+        if (p > (double)m) p = (double)m;
+        if (p < 0.0) p = 0.0;
+        p_out[g] = (float)p;
+    }
+    return REF_OK;
+}
+
+/* Mean squared error of Eq.3 for a given (m, p) per group, same arithmetic as
+ * the search (binary32 code, binary64 error). */
+int pwlq_ref_mse(const float *w, int64_t C, int64_t K, int bits, int mode, const float *p,
+                 const float *m_in, double *mse)
+{
+    if (!w || !p || !m_in || !mse) return REF_ENULL;
+    int rc = check_common(C, K, bits, mode);
+    if (rc) return rc;
+    int64_t G = (mode == REF_PER_CHANNEL) ? C : 1;
+    int64_t count = (mode == REF_PER_CHANNEL) ? K : C * K;
+#pragma omp parallel for schedule(static)
+    for (int64_t g = 0; g < G; ++g) {
+        pieces q = make_pieces(m_in[g], p[g], bits);
+        double sse = 0.0;
+        for (int64_t i = 0; i < count; ++i) {
+            double e = piece_error(&q, fabsf(w[g * count + i]));
+            sse += e * e;
+        }
+        mse[g] = sse / (double)count;
+    }
+    return REF_OK;
+}
+
 int pwlq_ref_num_threads(void)
 {
 #ifdef _OPENMP

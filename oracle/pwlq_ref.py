@@ -55,8 +55,46 @@ def lib() -> ctypes.CDLL:
         L.pwlq_ref_pack.argtypes = [bp, bp, ctypes.c_int64, ctypes.c_int, bp, bp]
         L.pwlq_ref_unpack.restype = ctypes.c_int
         L.pwlq_ref_unpack.argtypes = [bp, bp, ctypes.c_int64, ctypes.c_int, bp, bp]
+        L.pwlq_ref_select_analytic.restype = ctypes.c_int
+        L.pwlq_ref_select_analytic.argtypes = [fp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
+                                               ctypes.c_int, fp, fp]
+        L.pwlq_ref_mse.restype = ctypes.c_int
+        L.pwlq_ref_mse.argtypes = [fp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
+                                   fp, fp, dp]
         _lib = L
     return _lib
+
+
+GAUSS_FIT, GAUSS_SOLVE, LAPLACE_SOLVE = 0, 1, 2
+
+
+def select_analytic(w: np.ndarray, selector: int, mode: int = PER_CHANNEL):
+    """The paper's analytic breakpoint selectors.  Returns (p f32 [G], m f32 [G])."""
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    C, K = w.shape
+    G = C if mode == PER_CHANNEL else 1
+    p = np.empty(G, np.float32)
+    m = np.empty(G, np.float32)
+    rc = lib().pwlq_ref_select_analytic(_ptr(w, ctypes.c_float), C, K, mode, selector,
+                                        _ptr(p, ctypes.c_float), _ptr(m, ctypes.c_float))
+    if rc != 0:
+        raise ValueError(f"pwlq_ref_select_analytic status {rc}")
+    return p, m
+
+
+def mse(w: np.ndarray, bits: int, p: np.ndarray, m: np.ndarray, mode: int = PER_CHANNEL):
+    """Mean squared quantization error for given (m, p) per group (float64 [G])."""
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    C, K = w.shape
+    G = C if mode == PER_CHANNEL else 1
+    p = np.ascontiguousarray(p, dtype=np.float32)
+    m = np.ascontiguousarray(m, dtype=np.float32)
+    out = np.empty(G, np.float64)
+    rc = lib().pwlq_ref_mse(_ptr(w, ctypes.c_float), C, K, bits, mode, _ptr(p, ctypes.c_float),
+                            _ptr(m, ctypes.c_float), _ptr(out, ctypes.c_double))
+    if rc != 0:
+        raise ValueError(f"pwlq_ref_mse status {rc}")
+    return out
 
 
 def _ptr(a: np.ndarray, ctype):
