@@ -212,6 +212,42 @@ def main() -> int:
         "note": "call time (table upload + kernel), w_hat not requested",
     }
 
+    # The paper's analytic breakpoint selectors on the same weights: time of one
+    # model-level call and the error they reach relative to the exhaustive
+    # optimum of the step above (both errors evaluated by pwlq_mse_list).
+    ws_sel = torch.empty(max(256, pwlq.select_list_workspace_bytes(tl)), dtype=torch.uint8,
+                         device="cuda")
+    ws_mse = torch.empty(max(256, pwlq.mse_list_workspace_bytes(tl)), dtype=torch.uint8,
+                         device="cuda")
+    sel_out = (torch.empty(tl.n_groups, dtype=torch.float32, device="cuda"),
+               torch.empty(tl.n_groups, dtype=torch.float32, device="cuda"))
+    mse_out = torch.empty(tl.n_groups, dtype=torch.float64, device="cuda")
+    best = pwlq.mse_list(tl, wl.bits, out["p_star"], out["m"], workspace=ws_mse).clone()
+    result["analytic_selectors"] = {}
+    for name, sel in (("gauss_fit", pwlq.GAUSS_FIT), ("gauss_solve", pwlq.GAUSS_SOLVE),
+                      ("laplace_solve", pwlq.LAPLACE_SOLVE)):
+        for _ in range(2):
+            pwlq.select_analytic_list(tl, sel, workspace=ws_sel, out=sel_out)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            pwlq.select_analytic_list(tl, sel, workspace=ws_sel, out=sel_out)
+        e1.record()
+        for _ in range(reps):
+            pwlq.mse_list(tl, wl.bits, sel_out[0], sel_out[1], workspace=ws_mse, out=mse_out)
+        e2.record()
+        e2.synchronize()
+        ok = (best > 0) & torch.isfinite(best) & torch.isfinite(mse_out)
+        ratio = (mse_out[ok] / best[ok])
+        result["analytic_selectors"][name] = {
+            "select_ms": e0.elapsed_time(e1) / reps,
+            "mse_ms": e1.elapsed_time(e2) / reps,
+            "mse_over_grid_optimum_geomean": float(torch.exp(torch.log(ratio).mean())),
+            "mse_over_grid_optimum_max": float(ratio.max()),
+            "total_sse_over_grid_optimum": float(
+                (mse_out[ok] * tl.group_counts(ok)).sum() / (best[ok] * tl.group_counts(ok)).sum()),
+        }
+
     if not args.no_cpu_baseline:
         from oracle import pwlq_ref
         pwlq_ref.search(host[0][:2], wl.bits, 8, wl.mode)            # load the library

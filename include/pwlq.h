@@ -140,6 +140,58 @@ int pwlq_quantize_packed_list(const pwlq_tensor_desc *desc, int n_tensors, int b
                               const int64_t *flag_byte_offset, float *w_hat, void *workspace,
                               size_t workspace_bytes, void *stream);
 
+/*
+ * The paper's own breakpoint selectors (Section 3.3, Section 5.1): the group is
+ * assumed to follow a zero-mean Gaussian or Laplacian restricted to [-m, m],
+ * m = max|w|, and p minimises the expected error of Eq.6 over (0, m/2), i.e.
+ * solves Eq.11.  The scale is estimated about zero from the group itself
+ * (sigma^2 = mean w^2, beta = mean |w|), in binary64.
+ *   PWLQ_SELECT_GAUSS_FIT      Section 5.1's logarithmic fit for a normalized
+ *                              Gaussian, with breakpoint and range in units of
+ *                              sigma: p = sigma ln(0.8614 m/sigma + 0.6079)
+ *   PWLQ_SELECT_GAUSS_SOLVE    Eq.11 with the truncated Gaussian's F and f
+ *   PWLQ_SELECT_LAPLACE_SOLVE  Eq.11 with the truncated Laplacian's F and f
+ * Outputs, device arrays of G entries: p_out (the solution rounded to
+ * binary32) and m_out (absmax).  An all-zero group gets p = 0; a group whose
+ * absmax is NaN or infinite gets p = NaN.  Workspace: device, 256-byte aligned,
+ * at least pwlq_select[_list]_workspace_bytes(...) bytes.
+ */
+typedef enum {
+    PWLQ_SELECT_GAUSS_FIT = 0,
+    PWLQ_SELECT_GAUSS_SOLVE = 1,
+    PWLQ_SELECT_LAPLACE_SOLVE = 2
+} pwlq_selector;
+
+size_t pwlq_select_workspace_bytes(int64_t C, int64_t K, int mode);
+size_t pwlq_select_list_workspace_bytes(const pwlq_tensor_desc *desc, int n_tensors, int mode);
+
+int pwlq_select_analytic(const float *w, int64_t C, int64_t K, int mode, int selector,
+                         float *p_out, float *m_out, void *workspace, size_t workspace_bytes,
+                         void *stream);
+
+int pwlq_select_analytic_list(const pwlq_tensor_desc *desc, int n_tensors, int mode, int selector,
+                              float *p_out, float *m_out, void *workspace,
+                              size_t workspace_bytes, void *stream);
+
+/*
+ * Mean squared quantization error of Eq.3 at a given (m, p) per group (the
+ * quantity Eq.7 minimises, for any breakpoint, not only a grid point): codes
+ * decided in binary32 exactly as pwlq_quantize decides them, error
+ * step*code + offset - |w| and its sum in binary64, divided by the number of
+ * elements in the group.  p and m are device arrays of G entries indexed like
+ * the search outputs; mse is a device array of G binary64 values.  Workspace:
+ * device, 256-byte aligned, at least pwlq_mse[_list]_workspace_bytes(...) bytes.
+ */
+size_t pwlq_mse_workspace_bytes(int64_t C, int64_t K, int mode);
+size_t pwlq_mse_list_workspace_bytes(const pwlq_tensor_desc *desc, int n_tensors, int mode);
+
+int pwlq_mse(const float *w, int64_t C, int64_t K, int bits, int mode, const float *p,
+             const float *m, double *mse, void *workspace, size_t workspace_bytes, void *stream);
+
+int pwlq_mse_list(const pwlq_tensor_desc *desc, int n_tensors, int bits, int mode, const float *p,
+                  const float *m, double *mse, void *workspace, size_t workspace_bytes,
+                  void *stream);
+
 /* Text of the calling thread's last non-OK status ("" if none).  The storage
  * is thread-local and owned by the library. */
 const char *pwlq_last_error(void);

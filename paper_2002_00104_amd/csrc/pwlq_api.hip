@@ -40,8 +40,12 @@ struct Plan {
     int n = 0, nblk = 0, nwords = 0;
     // workspace offsets in bytes
     size_t off_recs = 0, off_prefix = 0, off_tile_max = 0, off_gm = 0, off_offsets = 0,
-           off_sorted = 0, off_sse32 = 0, off_mask = 0, off_part = 0, off_gsum = 0, total = 0;
+           off_sorted = 0, off_sse32 = 0, off_mask = 0, off_part = 0, off_gsum = 0,
+           off_stat_max = 0, off_stat_s2 = 0, off_stat_s1 = 0, total = 0;
 };
+
+// per-tile scratch beyond the tensor table
+enum Aux { kAuxNone = 0, kAuxStats = 1, kAuxMse = 2 };
 
 int check_common(int bits, int mode)
 {
@@ -51,10 +55,10 @@ int check_common(int bits, int mode)
     return PWLQ_OK;
 }
 
-// n_cand == 0 builds a quantize-only plan (no search scratch).
+// n_cand == 0 builds a plan without search scratch (quantizer, selectors, error).
 int build_plan(Plan &pl, const pwlq_tensor_desc *desc, int n_tensors, int n_cand, int mode,
                bool need_pointers, const int64_t *code_byte_offset = nullptr,
-               const int64_t *flag_byte_offset = nullptr)
+               const int64_t *flag_byte_offset = nullptr, Aux aux = kAuxNone)
 {
     if (!desc) return fail(PWLQ_ENULL, "tensor descriptor table is NULL");
     if (n_tensors < 1) return fail(PWLQ_EINVAL, "n_tensors=%d must be >= 1", n_tensors);
@@ -166,6 +170,13 @@ int build_plan(Plan &pl, const pwlq_tensor_desc *desc, int n_tensors, int n_cand
         pl.off_mask = take(sizeof(int) * (size_t)mgroups * (size_t)(n_cand + 1));
         pl.off_part = take(sizeof(double) * (size_t)parts * (size_t)n_cand);
         pl.off_gsum = take(sizeof(double) * (size_t)mgroups * (size_t)n_cand);
+    }
+    if (aux == kAuxStats) {
+        pl.off_stat_max = take(sizeof(float) * (size_t)tiles);
+        pl.off_stat_s2 = take(sizeof(double) * (size_t)tiles);
+        pl.off_stat_s1 = take(sizeof(double) * (size_t)tiles);
+    } else if (aux == kAuxMse) {
+        pl.off_stat_s2 = take(sizeof(double) * (size_t)tiles);
     }
     pl.total = off;
     return PWLQ_OK;
@@ -359,9 +370,119 @@ int run_quantize_packed(const pwlq_tensor_desc *desc, int n_tensors, int bits, i
     return launch_status("packed quantize launch");
 }
 
+int run_select(const pwlq_tensor_desc *desc, int n_tensors, int mode, int selector, float *p_out,
+               float *m_out, void *workspace, size_t workspace_bytes, void *stream_v)
+{
+    int rc = check_common(2, mode);
+    if (rc) return rc;
+    if (selector < PWLQ_SELECT_GAUSS_FIT || selector > PWLQ_SELECT_LAPLACE_SOLVE)
+        return fail(PWLQ_EINVAL, "selector=%d is not a pwlq_selector", selector);
+    if (!p_out || !m_out) return fail(PWLQ_ENULL, "an output pointer is NULL");
+    Plan pl;
+    rc = build_plan(pl, desc, n_tensors, 0, mode, true, nullptr, nullptr, kAuxStats);
+    if (rc) return rc;
+    rc = check_workspace(pl, workspace, workspace_bytes);
+    if (rc) return rc;
+    hipStream_t stream = (hipStream_t)stream_v;
+    char *ws = (char *)workspace;
+    Tables tb;
+    rc = upload_tables(pl, ws, stream, tb);
+    if (rc) return rc;
+    float *tile_max = (float *)(ws + pl.off_stat_max);
+    double *tile_s2 = (double *)(ws + pl.off_stat_s2);
+    double *tile_s1 = (double *)(ws + pl.off_stat_s1);
+    k_stats<<<(int)pl.n_tiles, kWG, 0, stream>>>(tb, tile_max, tile_s2, tile_s1);
+    k_select<<<(int)((pl.n_groups + kWG - 1) / kWG), kWG, 0, stream>>>(
+        tb, (int)pl.n_groups, selector, tile_max, tile_s2, tile_s1, p_out, m_out);
+    return launch_status("select launch");
+}
+
+int run_mse(const pwlq_tensor_desc *desc, int n_tensors, int bits, int mode, const float *p,
+            const float *m, double *mse, void *workspace, size_t workspace_bytes, void *stream_v)
+{
+    int rc = check_common(bits, mode);
+    if (rc) return rc;
+    if (!p || !m || !mse) return fail(PWLQ_ENULL, "an input or output pointer is NULL");
+    Plan pl;
+    rc = build_plan(pl, desc, n_tensors, 0, mode, true, nullptr, nullptr, kAuxMse);
+    if (rc) return rc;
+    rc = check_workspace(pl, workspace, workspace_bytes);
+    if (rc) return rc;
+    hipStream_t stream = (hipStream_t)stream_v;
+    char *ws = (char *)workspace;
+    Tables tb;
+    rc = upload_tables(pl, ws, stream, tb);
+    if (rc) return rc;
+    double *tile_sse = (double *)(ws + pl.off_stat_s2);
+    k_mse_tile<<<(int)pl.n_tiles, kWG, 0, stream>>>(tb, bits, p, m, tile_sse);
+    k_mse_final<<<(int)((pl.n_groups + kWG - 1) / kWG), kWG, 0, stream>>>(tb, (int)pl.n_groups,
+                                                                        tile_sse, mse);
+    return launch_status("mse launch");
+}
+
 } // namespace
 
 extern "C" {
+
+size_t pwlq_select_list_workspace_bytes(const pwlq_tensor_desc *desc, int n_tensors, int mode)
+{
+    if (check_common(2, mode)) return 0;
+    Plan pl;
+    if (build_plan(pl, desc, n_tensors, 0, mode, false, nullptr, nullptr, kAuxStats)) return 0;
+    return pl.total;
+}
+
+size_t pwlq_select_workspace_bytes(int64_t C, int64_t K, int mode)
+{
+    pwlq_tensor_desc d = {nullptr, C, K, 0, 0};
+    return pwlq_select_list_workspace_bytes(&d, 1, mode);
+}
+
+int pwlq_select_analytic_list(const pwlq_tensor_desc *desc, int n_tensors, int mode, int selector,
+                              float *p_out, float *m_out, void *workspace, size_t workspace_bytes,
+                              void *stream)
+{
+    return run_select(desc, n_tensors, mode, selector, p_out, m_out, workspace, workspace_bytes,
+                      stream);
+}
+
+int pwlq_select_analytic(const float *w, int64_t C, int64_t K, int mode, int selector,
+                         float *p_out, float *m_out, void *workspace, size_t workspace_bytes,
+                         void *stream)
+{
+    if (!w) return fail(PWLQ_ENULL, "w is NULL");
+    pwlq_tensor_desc d = {w, C, K, 0, 0};
+    return run_select(&d, 1, mode, selector, p_out, m_out, workspace, workspace_bytes, stream);
+}
+
+size_t pwlq_mse_list_workspace_bytes(const pwlq_tensor_desc *desc, int n_tensors, int mode)
+{
+    if (check_common(2, mode)) return 0;
+    Plan pl;
+    if (build_plan(pl, desc, n_tensors, 0, mode, false, nullptr, nullptr, kAuxMse)) return 0;
+    return pl.total;
+}
+
+size_t pwlq_mse_workspace_bytes(int64_t C, int64_t K, int mode)
+{
+    pwlq_tensor_desc d = {nullptr, C, K, 0, 0};
+    return pwlq_mse_list_workspace_bytes(&d, 1, mode);
+}
+
+int pwlq_mse_list(const pwlq_tensor_desc *desc, int n_tensors, int bits, int mode, const float *p,
+                  const float *m, double *mse, void *workspace, size_t workspace_bytes,
+                  void *stream)
+{
+    return run_mse(desc, n_tensors, bits, mode, p, m, mse, workspace, workspace_bytes, stream);
+}
+
+int pwlq_mse(const float *w, int64_t C, int64_t K, int bits, int mode, const float *p,
+             const float *m, double *mse, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!w) return fail(PWLQ_ENULL, "w is NULL");
+    pwlq_tensor_desc d = {w, C, K, 0, 0};
+    return run_mse(&d, 1, bits, mode, p, m, mse, workspace, workspace_bytes, stream);
+}
 
 size_t pwlq_search_list_workspace_bytes(const pwlq_tensor_desc *desc, int n_tensors, int bits,
                                         int n_cand, int mode)

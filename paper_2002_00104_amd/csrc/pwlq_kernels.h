@@ -14,9 +14,14 @@
 //   k_final        argmin for groups spread over several tiles
 //
 // and of one quantize call:  k_emit (HBM bound).
+//
+// The analytic selectors run k_stats (per-tile max, sum of squares, sum of
+// magnitudes) and k_select (one thread per group solves for p); the error at a
+// given (m, p) runs k_mse_tile and k_mse_final.
 #pragma once
 
 #include "pwlq_prep.h"
 #include "pwlq_search.h"
 #include "pwlq_refine.h"
 #include "pwlq_emit.h"
+#include "pwlq_select.h"

@@ -25,6 +25,9 @@ EXPORTS = (
     "pwlq_quantize_list_workspace_bytes", "pwlq_quantize_list",
     "pwlq_packed_code_bytes", "pwlq_packed_flag_bytes", "pwlq_quantize_packed",
     "pwlq_quantize_packed_list",
+    "pwlq_select_workspace_bytes", "pwlq_select_list_workspace_bytes", "pwlq_select_analytic",
+    "pwlq_select_analytic_list",
+    "pwlq_mse_workspace_bytes", "pwlq_mse_list_workspace_bytes", "pwlq_mse", "pwlq_mse_list",
     "pwlq_last_error", "pwlq_last_search_shape", "pwlq_profile_enable",
     "pwlq_profile_last_ms", "pwlq_kernel_name",
 )
@@ -72,6 +75,22 @@ def _load() -> ctypes.CDLL:
     lib.pwlq_quantize_packed_list.restype = ci
     lib.pwlq_quantize_packed_list.argtypes = [dp, ci, ci, ci, vp, vp, vp, ctypes.POINTER(i64), vp,
                                               ctypes.POINTER(i64), vp, vp, sz, vp]
+    lib.pwlq_select_workspace_bytes.restype = sz
+    lib.pwlq_select_workspace_bytes.argtypes = [i64, i64, ci]
+    lib.pwlq_select_list_workspace_bytes.restype = sz
+    lib.pwlq_select_list_workspace_bytes.argtypes = [dp, ci, ci]
+    lib.pwlq_select_analytic.restype = ci
+    lib.pwlq_select_analytic.argtypes = [vp, i64, i64, ci, ci, vp, vp, vp, sz, vp]
+    lib.pwlq_select_analytic_list.restype = ci
+    lib.pwlq_select_analytic_list.argtypes = [dp, ci, ci, ci, vp, vp, vp, sz, vp]
+    lib.pwlq_mse_workspace_bytes.restype = sz
+    lib.pwlq_mse_workspace_bytes.argtypes = [i64, i64, ci]
+    lib.pwlq_mse_list_workspace_bytes.restype = sz
+    lib.pwlq_mse_list_workspace_bytes.argtypes = [dp, ci, ci]
+    lib.pwlq_mse.restype = ci
+    lib.pwlq_mse.argtypes = [vp, i64, i64, ci, ci, vp, vp, vp, vp, sz, vp]
+    lib.pwlq_mse_list.restype = ci
+    lib.pwlq_mse_list.argtypes = [dp, ci, ci, ci, vp, vp, vp, vp, sz, vp]
     lib.pwlq_last_error.restype = ctypes.c_char_p
     lib.pwlq_last_error.argtypes = []
     lib.pwlq_last_search_shape.restype = None
@@ -174,6 +193,17 @@ class TensorList:
 
     def __len__(self) -> int:
         return len(self.tensors)
+
+    def group_counts(self, select: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """Elements per group (float64, device), in per-group array order."""
+        if not hasattr(self, "_counts"):
+            parts = []
+            for t in self.tensors:
+                C, K = t.shape
+                G = _n_groups(C, self.mode)
+                parts.append(torch.full((G,), float(C * K // G), dtype=torch.float64))
+            self._counts = torch.cat(parts).to(self.device)
+        return self._counts if select is None else self._counts[select]
 
 
 def search_list_workspace_bytes(tl: TensorList, bits: int, n_cand: int) -> int:
@@ -285,6 +315,76 @@ def quantize_packed_list(tl: "TensorList", bits: int, p_star: torch.Tensor, m: t
                                          w_hat.data_ptr() if w_hat is not None else None,
                                          workspace.data_ptr(), workspace.numel(), _stream()))
     return pc, pf, w_hat, layout
+
+
+GAUSS_FIT, GAUSS_SOLVE, LAPLACE_SOLVE = 0, 1, 2
+
+
+def select_analytic(w: torch.Tensor, selector: int, mode: int = PER_CHANNEL,
+                    workspace: Optional[torch.Tensor] = None):
+    """pwlq_select_analytic on one [C, K] tensor.  Returns (p f32 [G], m f32 [G])."""
+    w = _dev32(w)
+    C, K = w.shape
+    G = _n_groups(C, mode)
+    if workspace is None:
+        workspace = _workspace(lib.pwlq_select_workspace_bytes(C, K, mode), w.device)
+    p = torch.empty(G, dtype=torch.float32, device=w.device)
+    m = torch.empty(G, dtype=torch.float32, device=w.device)
+    _check(lib.pwlq_select_analytic(w.data_ptr(), C, K, mode, selector, p.data_ptr(),
+                                    m.data_ptr(), workspace.data_ptr(), workspace.numel(),
+                                    _stream()))
+    return p, m
+
+
+def select_list_workspace_bytes(tl: "TensorList") -> int:
+    return int(lib.pwlq_select_list_workspace_bytes(tl.desc, len(tl), tl.mode))
+
+
+def select_analytic_list(tl: "TensorList", selector: int,
+                         workspace: Optional[torch.Tensor] = None, out=None):
+    if workspace is None:
+        workspace = _workspace(select_list_workspace_bytes(tl), tl.device)
+    if out is None:
+        out = (torch.empty(tl.n_groups, dtype=torch.float32, device=tl.device),
+               torch.empty(tl.n_groups, dtype=torch.float32, device=tl.device))
+    p, m = out
+    _check(lib.pwlq_select_analytic_list(tl.desc, len(tl), tl.mode, selector, p.data_ptr(),
+                                         m.data_ptr(), workspace.data_ptr(), workspace.numel(),
+                                         _stream()))
+    return p, m
+
+
+def mse(w: torch.Tensor, bits: int, p: torch.Tensor, m: torch.Tensor, mode: int = PER_CHANNEL,
+        workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """pwlq_mse on one [C, K] tensor.  Returns f64 [G]."""
+    w = _dev32(w)
+    C, K = w.shape
+    G = _n_groups(C, mode)
+    for t in (p, m):
+        if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.numel() == G):
+            raise ValueError("p and m must be float32 device tensors with one entry per group")
+    if workspace is None:
+        workspace = _workspace(lib.pwlq_mse_workspace_bytes(C, K, mode), w.device)
+    out = torch.empty(G, dtype=torch.float64, device=w.device)
+    _check(lib.pwlq_mse(w.data_ptr(), C, K, bits, mode, p.data_ptr(), m.data_ptr(),
+                        out.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream()))
+    return out
+
+
+def mse_list_workspace_bytes(tl: "TensorList") -> int:
+    return int(lib.pwlq_mse_list_workspace_bytes(tl.desc, len(tl), tl.mode))
+
+
+def mse_list(tl: "TensorList", bits: int, p: torch.Tensor, m: torch.Tensor,
+             workspace: Optional[torch.Tensor] = None,
+             out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    if workspace is None:
+        workspace = _workspace(mse_list_workspace_bytes(tl), tl.device)
+    if out is None:
+        out = torch.empty(tl.n_groups, dtype=torch.float64, device=tl.device)
+    _check(lib.pwlq_mse_list(tl.desc, len(tl), bits, tl.mode, p.data_ptr(), m.data_ptr(),
+                             out.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream()))
+    return out
 
 
 def profile_enable(on: bool) -> None:
