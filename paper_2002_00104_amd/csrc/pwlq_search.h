@@ -53,15 +53,14 @@ __device__ inline float zone_one_region(const float *__restrict__ us, int begin,
 
 // The wavefront's own bucket: the region differs from lane to lane.  Written
 // as a branch so that the compiler runs the centre lanes and the tail lanes
-// under execution masks (cheaper than selecting three operands per lane); the
-// error is summed in candidate units.
-__device__ inline float zone_mixed(const float *__restrict__ us, int begin, int end, float kf,
-                                   float rc, float rt, float ct, float stepc, float stept)
+// under execution masks (cheaper than selecting three operands per lane); each
+// region keeps its own sum in steps, scaled with the others at the end.
+__device__ inline void zone_mixed(const float *__restrict__ us, int begin, int end, float kf,
+                                  float rc, float rt, float ct, float &sum_c, float &sum_t)
 {
-    float outer = 0.0f;
     for (int cb = begin; cb < end; cb += kChunk) {
         const int ce = (cb + kChunk < end) ? cb + kChunk : end;
-        float acc = 0.0f;
+        float acc_c = 0.0f, acc_t = 0.0f;
         for (int i = cb; i < ce; i += kVec) {
             const float8 cur = load8(us + i);
 #pragma unroll
@@ -69,18 +68,18 @@ __device__ inline float zone_mixed(const float *__restrict__ us, int begin, int 
                 const float u = cur[e];
                 if (u > kf) {
                     const float t = __builtin_fmaf(u, rt, ct);
-                    const float err = (t - __builtin_rintf(t)) * stept;
-                    acc = __builtin_fmaf(err, err, acc);
+                    const float f = t - __builtin_rintf(t);
+                    acc_t = __builtin_fmaf(f, f, acc_t);
                 } else {
                     const float t = u * rc;
-                    const float err = (t - __builtin_rintf(t)) * stepc;
-                    acc = __builtin_fmaf(err, err, acc);
+                    const float f = t - __builtin_rintf(t);
+                    acc_c = __builtin_fmaf(f, f, acc_c);
                 }
             }
         }
-        outer += acc;
+        sum_c += acc_c;
+        sum_t += acc_t;
     }
-    return outer;
 }
 
 __global__ __launch_bounds__(kSearchWaves * 64) void k_search(Tables tb, int n, int nblk, int bits,
@@ -129,11 +128,11 @@ __global__ __launch_bounds__(kSearchWaves * 64) void k_search(Tables tb, int n, 
         const int *off = offsets + (long long)t * (nblk + 1);
         const int lo = off[j] & ~(kVec - 1);
         const int hi = (off[j + 1] + kVec - 1) & ~(kVec - 1);
-        const float sc = zone_one_region<false>(us, 0, lo, rc, 0.0f);
-        const float sm = zone_mixed(us, lo, hi, kf, rc, rt, ct, stepc, stept);
-        const float st = zone_one_region<true>(us, hi, padded, rt, ct);
+        float sc = zone_one_region<false>(us, 0, lo, rc, 0.0f);
+        float st = zone_one_region<true>(us, hi, padded, rt, ct);
+        zone_mixed(us, lo, hi, kf, rc, rt, ct, sc, st);
         if (live)
-            sse32[(long long)t * n + (k - 1)] = (stepc * stepc) * sc + (stept * stept) * st + sm;
+            sse32[(long long)t * n + (k - 1)] = (stepc * stepc) * sc + (stept * stept) * st;
     }
 }
 
