@@ -76,6 +76,24 @@ int pwlq_search(const float *w, int64_t C, int64_t K, int bits, int n_cand, int 
                 void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The same search with the same outputs, computed with less work: for tiles
+ * long enough to pay for it, a candidate's squared error is obtained from
+ * cumulative counts and sums of the magnitudes (2^b - 1 look-ups per
+ * candidate, independent of the group's length) instead of a pass over the
+ * group; the candidates this filter cannot tell apart are then re-evaluated
+ * exactly as in pwlq_search, so k_star, p_star and mse follow the same
+ * definition (Eq.7 on the group's own values).  Arguments and workspace size
+ * as for pwlq_search / pwlq_search_list.
+ */
+int pwlq_search_fast(const float *w, int64_t C, int64_t K, int bits, int n_cand, int mode,
+                     float *p_star, float *m_out, int32_t *k_star, double *mse,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+int pwlq_search_fast_list(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand,
+                          int mode, float *p_star, float *m_out, int32_t *k_star, double *mse,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Quantizer: Eq.3 with given (m, p) per group.  Device outputs of C*K entries:
  *   codes  b-bit sign-magnitude in one byte: bit b-1 is the sign, bits 0..b-2
  *          the piece's code 0..2^(b-1)-1 (Section 3.2: b bits including sign)
@@ -203,14 +221,15 @@ void pwlq_last_search_shape(int64_t *n_tiles, int64_t *n_groups, int64_t *n_unit
 /* Benchmark aid.  With profiling enabled every search / quantize call records
  * HIP events on its own stream right before and after its dominant kernel
  * (role 0: the candidate-evaluation kernel of a search; role 1: the quantize
- * kernel).  pwlq_profile_last_ms waits for the later event of the most recent
+ * kernel; role 2: the prefix-sum evaluation kernel of a fast search).  pwlq_profile_last_ms waits for the later event of the most recent
  * call and returns the kernel's duration in milliseconds, or -1 if none was
  * recorded.  Process-wide, not thread-safe; off by default. */
 void pwlq_profile_enable(int on);
 double pwlq_profile_last_ms(int role);
 
 /* Name of the library's kernels as they appear in a kernel trace, by role:
- * 0 search (dominant), 1 quantize.  Returns NULL for other roles. */
+ * 0 search (dominant), 1 quantize, 2 prefix-sum evaluation.  Returns NULL for
+ * other roles. */
 const char *pwlq_kernel_name(int role);
 
 #ifdef __cplusplus

@@ -58,7 +58,8 @@ int check_common(int bits, int mode)
 // n_cand == 0 builds a plan without search scratch (quantizer, selectors, error).
 int build_plan(Plan &pl, const pwlq_tensor_desc *desc, int n_tensors, int n_cand, int mode,
                bool need_pointers, const int64_t *code_byte_offset = nullptr,
-               const int64_t *flag_byte_offset = nullptr, Aux aux = kAuxNone)
+               const int64_t *flag_byte_offset = nullptr, Aux aux = kAuxNone,
+               int fast_min_len = 0)
 {
     if (!desc) return fail(PWLQ_ENULL, "tensor descriptor table is NULL");
     if (n_tensors < 1) return fail(PWLQ_EINVAL, "n_tensors=%d must be >= 1", n_tensors);
@@ -98,6 +99,7 @@ int build_plan(Plan &pl, const pwlq_tensor_desc *desc, int n_tensors, int n_cand
         r.ntiles = (int)(groups * tpg);
         r.stride = (r.tile_len + kVec - 1) / kVec * kVec + kVec;   // one spare vector: loads may run one ahead
         r.tpu = std::max(1, kUnitElems / r.tile_len);
+        r.fast = (fast_min_len > 0 && r.tile_len >= fast_min_len) ? 1 : 0;
         tmp[i] = r;
         order[i] = {i, r.tile_len};
     }
@@ -139,7 +141,7 @@ int build_plan(Plan &pl, const pwlq_tensor_desc *desc, int n_tensors, int n_cand
         groups += r.ngroups;
         units += (r.ntiles + r.tpu - 1) / r.tpu;
         if (r.tpg > 1) { mgroups += r.ngroups; parts += r.ntiles; }
-        sorted += (long long)r.ntiles * r.stride;
+        if (!r.fast) sorted += (long long)r.ntiles * r.stride;
         if (tiles > 0x3fffffffLL || units > 0x3fffffffLL || chunks > 0x3fffffffLL)
             return fail(PWLQ_EINVAL, "call has too many tiles");
         pl.recs[s] = r;
@@ -236,9 +238,9 @@ int launch_status(const char *what)
 
 // Optional event timing of the dominant kernels (benchmarks only).
 bool g_profile = false;
-hipEvent_t g_ev[4];
+hipEvent_t g_ev[6];
 bool g_ev_made = false;
-bool g_ev_valid[2] = {false, false};
+bool g_ev_valid[3] = {false, false, false};
 
 void profile_mark(int idx, hipStream_t stream)
 {
@@ -251,16 +253,27 @@ void profile_mark(int idx, hipStream_t stream)
     if (idx & 1) g_ev_valid[idx >> 1] = true;
 }
 
+// Shortest tile handed to the prefix-sum evaluator by the fast search: its
+// cost per candidate grows with the number of levels (2L+1 look-ups) and does
+// not depend on the tile length, the plain evaluation costs one pass over the
+// tile.
+int fast_min_len(int bits)
+{
+    const int L = (1 << (bits - 1)) - 1;
+    return 16 * (2 * L + 1) + 64;
+}
+
 int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand, int mode,
                float *p_star, float *m_out, int32_t *k_star, double *mse, void *workspace,
-               size_t workspace_bytes, void *stream_v)
+               size_t workspace_bytes, void *stream_v, bool fast = false)
 {
     int rc = check_common(bits, mode);
     if (rc) return rc;
     if (n_cand < 1 || n_cand > 65535) return fail(PWLQ_EINVAL, "n_cand=%d outside [1,65535]", n_cand);
     if (!p_star || !m_out || !k_star || !mse) return fail(PWLQ_ENULL, "an output pointer is NULL");
     Plan pl;
-    rc = build_plan(pl, desc, n_tensors, n_cand, mode, true);
+    rc = build_plan(pl, desc, n_tensors, n_cand, mode, true, nullptr, nullptr, kAuxNone,
+                    fast ? fast_min_len(bits) : 0);
     if (rc) return rc;
     rc = check_workspace(pl, workspace, workspace_bytes);
     if (rc) return rc;
@@ -287,20 +300,48 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
 
     const int NT = (int)pl.n_tiles;
     if (pl.n_mgroups > 0) k_tile_absmax<<<NT, kWG, 0, stream>>>(tb, tile_max);
-    int longest = 0;
-    for (const TensorRec &r : pl.recs) longest = std::max(longest, r.tile_len);
-    const size_t stage_bytes = sizeof(float) * (size_t)((longest + kVec - 1) / kVec * kVec);
-    if (pl.nblk <= 32) {
-        k_prep<true><<<NT, kWG, sizeof(int) * ((pl.nblk + 1) / 2) * kWG + stage_bytes, stream>>>(
-            tb, n_cand, pl.nblk, tile_max, gm, offsets, sorted);
-    } else {
-        k_prep<false><<<NT, kWG, sizeof(int) * pl.nblk + stage_bytes, stream>>>(
-            tb, n_cand, pl.nblk, tile_max, gm, offsets, sorted);
+    int longest = 0, longest_fast = 0, fast_tiles = 0;
+    for (const TensorRec &r : pl.recs) {
+        if (r.fast) { longest_fast = std::max(longest_fast, r.tile_len); fast_tiles += r.ntiles; }
+        else longest = std::max(longest, r.tile_len);
     }
-    profile_mark(0, stream);
-    k_search<<<(unsigned)wgs, kSearchWaves * 64, 0, stream>>>(tb, n_cand, pl.nblk, bits, ny,
-                                                offsets, sorted, sse32);
-    profile_mark(1, stream);
+    if (fast_tiles > 0) {
+        // tensors are ordered longest tile first, so the fast tiles are 0 .. fast_tiles-1
+        int tcap = 64;
+        while (tcap < kFastTMax && 2 * tcap <= longest_fast) tcap <<= 1;
+        const size_t lds = sizeof(double) * (size_t)(tcap + 1 + tcap / kFastP2Step + 1) +
+                           sizeof(unsigned short) * (size_t)(tcap + 2) +
+                           sizeof(float) * (size_t)longest_fast;
+        if (lds > 64 * 1024) {
+            static bool raised = false;          // more than 64 KiB of LDS must be asked for
+            if (!raised) {
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fast),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                   128 * 1024);
+                if (e != hipSuccess)
+                    return fail(PWLQ_EHIP, "LDS limit of the prefix-sum kernel: %s",
+                                hipGetErrorString(e));
+                raised = true;
+            }
+        }
+        profile_mark(4, stream);
+        k_fast<<<fast_tiles, kFastWG, lds, stream>>>(tb, n_cand, bits, tcap, tile_max, gm, sse32);
+        profile_mark(5, stream);
+    }
+    if (fast_tiles < NT) {
+        const size_t stage_bytes = sizeof(float) * (size_t)((longest + kVec - 1) / kVec * kVec);
+        if (pl.nblk <= 32) {
+            k_prep<true><<<NT, kWG, sizeof(int) * ((pl.nblk + 1) / 2) * kWG + stage_bytes, stream>>>(
+                tb, n_cand, pl.nblk, tile_max, gm, offsets, sorted);
+        } else {
+            k_prep<false><<<NT, kWG, sizeof(int) * pl.nblk + stage_bytes, stream>>>(
+                tb, n_cand, pl.nblk, tile_max, gm, offsets, sorted);
+        }
+        profile_mark(0, stream);
+        k_search<<<(unsigned)wgs, kSearchWaves * 64, 0, stream>>>(tb, n_cand, pl.nblk, bits, ny,
+                                                    offsets, sorted, sse32);
+        profile_mark(1, stream);
+    }
     if (pl.n_mgroups > 0) {
         k_group_sum<<<dim3((n_cand + kWG - 1) / kWG, (unsigned)pl.n_mgroups), kWG, 0, stream>>>(
             tb, n_cand, sse32, gsum);
@@ -517,6 +558,24 @@ int pwlq_search(const float *w, int64_t C, int64_t K, int bits, int n_cand, int 
                       workspace_bytes, stream);
 }
 
+int pwlq_search_fast_list(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand,
+                          int mode, float *p_star, float *m_out, int32_t *k_star, double *mse,
+                          void *workspace, size_t workspace_bytes, void *stream)
+{
+    return run_search(desc, n_tensors, bits, n_cand, mode, p_star, m_out, k_star, mse, workspace,
+                      workspace_bytes, stream, true);
+}
+
+int pwlq_search_fast(const float *w, int64_t C, int64_t K, int bits, int n_cand, int mode,
+                     float *p_star, float *m_out, int32_t *k_star, double *mse, void *workspace,
+                     size_t workspace_bytes, void *stream)
+{
+    if (!w) return fail(PWLQ_ENULL, "w is NULL");
+    pwlq_tensor_desc d = {w, C, K, 0, 0};
+    return run_search(&d, 1, bits, n_cand, mode, p_star, m_out, k_star, mse, workspace,
+                      workspace_bytes, stream, true);
+}
+
 size_t pwlq_quantize_list_workspace_bytes(const pwlq_tensor_desc *desc, int n_tensors, int bits,
                                           int mode)
 {
@@ -577,7 +636,7 @@ void pwlq_profile_enable(int on) { g_profile = on != 0; }
 
 double pwlq_profile_last_ms(int role)
 {
-    if (role < 0 || role > 1 || !g_ev_made || !g_ev_valid[role]) return -1.0;
+    if (role < 0 || role > 2 || !g_ev_made || !g_ev_valid[role]) return -1.0;
     float ms = -1.0f;
     if (hipEventSynchronize(g_ev[2 * role + 1]) != hipSuccess) return -1.0;
     if (hipEventElapsedTime(&ms, g_ev[2 * role], g_ev[2 * role + 1]) != hipSuccess) return -1.0;
@@ -595,6 +654,7 @@ const char *pwlq_kernel_name(int role)
 {
     if (role == 0) return "k_search";
     if (role == 1) return "k_emit";
+    if (role == 2) return "k_fast";
     return nullptr;
 }
 

@@ -14,7 +14,10 @@ namespace pwlq {
 constexpr int kWG = 256;          // threads per workgroup (4 wavefronts of 64)
 constexpr int kWaves = kWG / 64;
 constexpr int kBlk = 64;          // candidates per wavefront: lane = candidate
-constexpr int kSearchWaves = 16;  // wavefronts (candidate blocks) per search workgroup
+#ifndef PWLQ_SEARCH_WAVES
+#define PWLQ_SEARCH_WAVES 16
+#endif
+constexpr int kSearchWaves = PWLQ_SEARCH_WAVES;  // wavefronts (candidate blocks) per search workgroup
 constexpr int kTileMax = 8192;    // longest run of a group handled by one workgroup
 constexpr int kPerThread = kTileMax / kWG;  // elements of a tile held by one thread
 constexpr int kUnitElems = 4096;  // small tiles are batched up to about this many elements
@@ -39,6 +42,7 @@ struct TensorRec {
     int tile_base, group_base, unit_base, mgroup_base;
     int emit_base;         // first chunk of this tensor in the quantize kernel's grid
     int ntiles, ngroups;
+    int fast;              // tiles evaluated by the prefix-sum kernel instead of prep + search
 };
 
 struct TileInfo {

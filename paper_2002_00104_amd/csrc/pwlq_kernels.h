@@ -25,3 +25,4 @@
 #include "pwlq_refine.h"
 #include "pwlq_emit.h"
 #include "pwlq_select.h"
+#include "pwlq_fast.h"

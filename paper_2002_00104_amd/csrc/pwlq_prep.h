@@ -76,6 +76,7 @@ __global__ __launch_bounds__(kWG) void k_prep(Tables tb, int n, int nblk,
     const int wave = tid >> 6;
     TensorRec r;
     TileInfo ti = tile_of(tb, t, r);
+    if (r.fast) return;               // evaluated by k_fast
     const int len = ti.len;
 
     float a[kPerThread];

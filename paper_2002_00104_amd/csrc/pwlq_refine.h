@@ -11,10 +11,14 @@ namespace pwlq {
 // candidate within the rounding slack of the minimum is kept and re-evaluated
 // exactly.  The slack bounds twice the error of k_search: eps = 2^-21 n per
 // element error (candidate units) and 3e-5 relative for the binary32 sums.
-__device__ inline double keep_threshold(double mn, double count, int n)
+// Tiles evaluated by prefix sums add the bound of that arithmetic
+// (kFastRelErr n^2 per element).
+constexpr double kFastRelErr = 3.0e-11;
+__device__ inline double keep_threshold(double mn, double count, int n, bool fast)
 {
     const double eps = (double)n * 4.76837158203125e-07;   // 2^-21 n
-    return mn + 2.0 * (3e-5 * mn + 2.0 * eps * sqrt(count * mn) + count * eps * eps);
+    const double extra = fast ? kFastRelErr * (double)n * (double)n * count : 0.0;
+    return mn + 2.0 * (3e-5 * mn + 2.0 * eps * sqrt(count * mn) + count * eps * eps + extra);
 }
 
 // Groups spread over several tiles, step 1: add the tiles' binary32 sums in
@@ -67,7 +71,7 @@ __global__ __launch_bounds__(kWG) void k_flag(Tables tb, int n,
     double mn = __builtin_inf();
     for (int k0 = tid; k0 < n; k0 += kWG) mn = fmin(mn, row[k0]);
     mn = block_min(mn, lds);
-    const double thr = keep_threshold(mn, (double)r.gcount, n);
+    const double thr = keep_threshold(mn, (double)r.gcount, n, r.fast != 0);
     int total = 0;
     for (int base = 0; base < n; base += kWG) {
         const int k0 = base + tid;
@@ -227,7 +231,7 @@ __device__ inline void exact_body(const TensorRec &r, const TileInfo &ti, int t,
         double mn = __builtin_inf();
         for (int k0 = tid; k0 < n; k0 += kWG) mn = fmin(mn, (double)row[k0]);
         mn = block_min(mn, lds);
-        const double thr = keep_threshold(mn, (double)r.gcount, n);
+        const double thr = keep_threshold(mn, (double)r.gcount, n, r.fast != 0);
         for (int rbase = 0; rbase < n; rbase += kListCap) {
             __syncthreads();
             if (tid == 0) *lcount = 0;

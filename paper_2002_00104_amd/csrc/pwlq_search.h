@@ -51,35 +51,35 @@ __device__ inline float zone_one_region(const float *__restrict__ us, int begin,
     return outer;
 }
 
-// The wavefront's own bucket: the region differs from lane to lane.  Written
-// as a branch so that the compiler runs the centre lanes and the tail lanes
-// under execution masks (cheaper than selecting three operands per lane); each
-// region keeps its own sum in steps, scaled with the others at the end.
-__device__ inline void zone_mixed(const float *__restrict__ us, int begin, int end, float kf,
-                                  float rc, float rt, float ct, float &sum_c, float &sum_t)
+// The wavefront's own bucket: the region differs from lane to lane.  Both
+// positions are computed and selected per lane (compare, two selects); masking
+// the two regions one after the other costs more, because every change of the
+// execution mask waits for the comparison.  The error is summed in candidate
+// units.
+__device__ inline float zone_mixed(const float *__restrict__ us, int begin, int end, float kf,
+                                   float rc, float rt, float ct, float stepc, float stept)
 {
+    float outer = 0.0f;
     for (int cb = begin; cb < end; cb += kChunk) {
         const int ce = (cb + kChunk < end) ? cb + kChunk : end;
-        float acc_c = 0.0f, acc_t = 0.0f;
+        float acc = 0.0f;
         for (int i = cb; i < ce; i += kVec) {
             const float8 cur = load8(us + i);
 #pragma unroll
             for (int e = 0; e < kVec; ++e) {
                 const float u = cur[e];
-                if (u > kf) {
-                    const float t = __builtin_fmaf(u, rt, ct);
-                    const float f = t - __builtin_rintf(t);
-                    acc_t = __builtin_fmaf(f, f, acc_t);
-                } else {
-                    const float t = u * rc;
-                    const float f = t - __builtin_rintf(t);
-                    acc_c = __builtin_fmaf(f, f, acc_c);
-                }
+                const bool tail = u > kf;
+                const float tc = u * rc;
+                const float tt = __builtin_fmaf(u, rt, ct);
+                const float t = tail ? tt : tc;
+                const float step = tail ? stept : stepc;
+                const float err = (t - __builtin_rintf(t)) * step;
+                acc = __builtin_fmaf(err, err, acc);
             }
         }
-        sum_c += acc_c;
-        sum_t += acc_t;
+        outer += acc;
     }
+    return outer;
 }
 
 __global__ __launch_bounds__(kSearchWaves * 64) void k_search(Tables tb, int n, int nblk, int bits,
@@ -102,6 +102,7 @@ __global__ __launch_bounds__(kSearchWaves * 64) void k_search(Tables tb, int n, 
 
     const int tensor = find_tensor(tb.unit_prefix, tb.nt, unit);
     const TensorRec r = rec_of(tb, tensor);
+    if (r.fast) return;               // evaluated by k_fast
     const int first = r.tile_base + (unit - r.unit_base) * r.tpu;
     int last = first + r.tpu;
     if (last > r.tile_base + r.ntiles) last = r.tile_base + r.ntiles;
@@ -128,11 +129,11 @@ __global__ __launch_bounds__(kSearchWaves * 64) void k_search(Tables tb, int n, 
         const int *off = offsets + (long long)t * (nblk + 1);
         const int lo = off[j] & ~(kVec - 1);
         const int hi = (off[j + 1] + kVec - 1) & ~(kVec - 1);
-        float sc = zone_one_region<false>(us, 0, lo, rc, 0.0f);
-        float st = zone_one_region<true>(us, hi, padded, rt, ct);
-        zone_mixed(us, lo, hi, kf, rc, rt, ct, sc, st);
+        const float sc = zone_one_region<false>(us, 0, lo, rc, 0.0f);
+        const float sm = zone_mixed(us, lo, hi, kf, rc, rt, ct, stepc, stept);
+        const float st = zone_one_region<true>(us, hi, padded, rt, ct);
         if (live)
-            sse32[(long long)t * n + (k - 1)] = (stepc * stepc) * sc + (stept * stept) * st;
+            sse32[(long long)t * n + (k - 1)] = (stepc * stepc) * sc + (stept * stept) * st + sm;
     }
 }
 

@@ -51,6 +51,7 @@ __device__ inline TensorRec rec_of(const Tables &tb, int i)
     r.emit_base = uni(r.emit_base);
     r.ntiles = uni(r.ntiles);
     r.ngroups = uni(r.ngroups);
+    r.fast = uni(r.fast);
     return r;
 }
 __device__ inline TileInfo tile_of(const Tables &tb, int t, TensorRec &r)

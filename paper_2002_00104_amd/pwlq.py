@@ -22,6 +22,7 @@ LIB_PATH = os.path.join(_HERE, "libpwlq.so")
 EXPORTS = (
     "pwlq_search_workspace_bytes", "pwlq_search", "pwlq_quantize",
     "pwlq_search_list_workspace_bytes", "pwlq_search_list",
+    "pwlq_search_fast", "pwlq_search_fast_list",
     "pwlq_quantize_list_workspace_bytes", "pwlq_quantize_list",
     "pwlq_packed_code_bytes", "pwlq_packed_flag_bytes", "pwlq_quantize_packed",
     "pwlq_quantize_packed_list",
@@ -56,12 +57,16 @@ def _load() -> ctypes.CDLL:
     lib.pwlq_search_workspace_bytes.argtypes = [i64, i64, ci, ci, ci]
     lib.pwlq_search.restype = ci
     lib.pwlq_search.argtypes = [vp, i64, i64, ci, ci, ci, vp, vp, vp, vp, vp, sz, vp]
+    lib.pwlq_search_fast.restype = ci
+    lib.pwlq_search_fast.argtypes = lib.pwlq_search.argtypes
     lib.pwlq_quantize.restype = ci
     lib.pwlq_quantize.argtypes = [vp, i64, i64, ci, ci, vp, vp, vp, vp, vp, vp]
     lib.pwlq_search_list_workspace_bytes.restype = sz
     lib.pwlq_search_list_workspace_bytes.argtypes = [dp, ci, ci, ci, ci]
     lib.pwlq_search_list.restype = ci
     lib.pwlq_search_list.argtypes = [dp, ci, ci, ci, ci, vp, vp, vp, vp, vp, sz, vp]
+    lib.pwlq_search_fast_list.restype = ci
+    lib.pwlq_search_fast_list.argtypes = lib.pwlq_search_list.argtypes
     lib.pwlq_quantize_list_workspace_bytes.restype = sz
     lib.pwlq_quantize_list_workspace_bytes.argtypes = [dp, ci, ci, ci]
     lib.pwlq_quantize_list.restype = ci
@@ -135,8 +140,9 @@ def search_workspace_bytes(C: int, K: int, bits: int, n_cand: int, mode: int) ->
 
 
 def search(w: torch.Tensor, bits: int, n_cand: int, mode: int = PER_CHANNEL,
-           workspace: Optional[torch.Tensor] = None) -> Dict[str, torch.Tensor]:
-    """pwlq_search on one [C, K] tensor.  Returns p_star, m, k_star, mse (device)."""
+           workspace: Optional[torch.Tensor] = None, fast: bool = False) -> Dict[str, torch.Tensor]:
+    """pwlq_search (or pwlq_search_fast) on one [C, K] tensor.
+    Returns p_star, m, k_star, mse (device)."""
     w = _dev32(w)
     C, K = w.shape
     G = _n_groups(C, mode)
@@ -146,9 +152,10 @@ def search(w: torch.Tensor, bits: int, n_cand: int, mode: int = PER_CHANNEL,
                m=torch.empty(G, dtype=torch.float32, device=w.device),
                k_star=torch.empty(G, dtype=torch.int32, device=w.device),
                mse=torch.empty(G, dtype=torch.float64, device=w.device))
-    _check(lib.pwlq_search(w.data_ptr(), C, K, bits, n_cand, mode, out["p_star"].data_ptr(),
-                           out["m"].data_ptr(), out["k_star"].data_ptr(), out["mse"].data_ptr(),
-                           workspace.data_ptr(), workspace.numel(), _stream()))
+    fn = lib.pwlq_search_fast if fast else lib.pwlq_search
+    _check(fn(w.data_ptr(), C, K, bits, n_cand, mode, out["p_star"].data_ptr(),
+              out["m"].data_ptr(), out["k_star"].data_ptr(), out["mse"].data_ptr(),
+              workspace.data_ptr(), workspace.numel(), _stream()))
     return out
 
 
@@ -212,15 +219,16 @@ def search_list_workspace_bytes(tl: TensorList, bits: int, n_cand: int) -> int:
 
 def search_list(tl: TensorList, bits: int, n_cand: int,
                 workspace: Optional[torch.Tensor] = None,
-                out: Optional[Dict[str, torch.Tensor]] = None) -> Dict[str, torch.Tensor]:
+                out: Optional[Dict[str, torch.Tensor]] = None,
+                fast: bool = False) -> Dict[str, torch.Tensor]:
     if workspace is None:
         workspace = _workspace(search_list_workspace_bytes(tl, bits, n_cand), tl.device)
     if out is None:
         out = alloc_search_outputs(tl.n_groups, tl.device)
-    _check(lib.pwlq_search_list(tl.desc, len(tl), bits, n_cand, tl.mode, out["p_star"].data_ptr(),
-                                out["m"].data_ptr(), out["k_star"].data_ptr(),
-                                out["mse"].data_ptr(), workspace.data_ptr(), workspace.numel(),
-                                _stream()))
+    fn = lib.pwlq_search_fast_list if fast else lib.pwlq_search_list
+    _check(fn(tl.desc, len(tl), bits, n_cand, tl.mode, out["p_star"].data_ptr(),
+              out["m"].data_ptr(), out["k_star"].data_ptr(), out["mse"].data_ptr(),
+              workspace.data_ptr(), workspace.numel(), _stream()))
     return out
 
 

@@ -43,6 +43,10 @@ def run_both(P, w, bits, n, mode, what):
     g = to_np(g)
     r = R.search(w, bits, n, mode, want_curve=True)
     stats = assert_search_matches(g, r, what)
+    # the prefix-sum search must meet the same definition
+    gf = P.search(wd, bits, n, mode, fast=True)
+    torch.cuda.synchronize()
+    assert_search_matches(to_np(gf), r, what + " (fast)")
     # quantize with the oracle's parameters on both sides, so a legitimate
     # near-tie difference in k* cannot leak into the code comparison
     ps, ms = r["p_star"].copy(), r["m"].copy()
@@ -186,6 +190,9 @@ def _list_case(P, tensors, bits, n, mode, what, check_groups=None):
     out = P.search_list(tl, bits, n)
     torch.cuda.synchronize()
     say(f"  search done, shape {P.last_search_shape()}")
+    fast = to_np(P.search_list(tl, bits, n, fast=True))
+    torch.cuda.synchronize()
+    say("  fast search done")
     codes, flags, w_hat = P.quantize_list(tl, bits, out["p_star"], out["m"])
     torch.cuda.synchronize()
     say("  quantize done")
@@ -199,6 +206,8 @@ def _list_case(P, tensors, bits, n, mode, what, check_groups=None):
             r = R.search(w, bits, n, mode, want_curve=True)
             gs = {k: v[go:go + 1] for k, v in g.items()}
             assert_search_matches(gs, r, f"{what} tensor {ti}")
+            assert_search_matches({k: v[go:go + 1] for k, v in fast.items()}, r,
+                                  f"{what} tensor {ti} (fast)")
             sl = slice(eo, eo + C * K)
             got = tuple(t[sl].cpu().numpy().reshape(C, K) for t in (codes, flags, w_hat))
             want = R.quantize(w, bits, gs["p_star"], gs["m"], mode)
@@ -208,6 +217,8 @@ def _list_case(P, tensors, bits, n, mode, what, check_groups=None):
             r = R.search(w[rows], bits, n, mode, want_curve=True)
             gs = {k: v[go + rows] for k, v in g.items()}
             assert_search_matches(gs, r, f"{what} tensor {ti}")
+            assert_search_matches({k: v[go + rows] for k, v in fast.items()}, r,
+                                  f"{what} tensor {ti} (fast)")
             got = tuple(t[eo:eo + C * K].view(C, K)[torch.from_numpy(rows).cuda()].cpu().numpy()
                         for t in (codes, flags, w_hat))
             want = R.quantize(w[rows], bits, gs["p_star"], gs["m"], mode)
