@@ -29,6 +29,7 @@ constexpr int kFastWG = 512;                       // threads per workgroup
 constexpr int kFastWaves = kFastWG / 64;
 constexpr int kFastPer = kTileMax / kFastWG;       // elements of a tile held by one thread
 constexpr int kFastTMax = 2048;                    // most buckets per tile
+constexpr int kFastCrowd = 48;                     // fullest bucket the look-ups are allowed to walk
 
 // Error of a tile's filter value from the binary64 prefix arithmetic: every
 // cumulative sum is within (tile length + 64) * 2^-53 of its magnitude (at most
@@ -77,10 +78,9 @@ __device__ inline void fast_query(const FastLds &L, float b, int &count, double 
     double a1 = L.P1[c];
     for (int i = st; i < en; ++i) {
         const float u = L.elems[i];
-        if (u <= b) {
-            ++nn;
-            a1 += (double)u;
-        }
+        const bool le = u <= b;
+        nn += le ? 1 : 0;
+        a1 += le ? (double)u : 0.0;
     }
     count = nn;
     s1 = a1;
@@ -120,14 +120,14 @@ __device__ inline void fast_candidates(const FastLds &Q, int n, int len, int Li,
         const double kd = (double)k;
         // centre piece: offset 0, step k/L
         double sumC = 0.0;
-        long long sumN = 0;
+        int sumN = 0;          // at most L^2 K < 2^31
         int cn;
         double c1;
         const double half_c = kd / (2.0 * Ld);
         for (int j = 0; j < Li; ++j) {
             fast_query(Q, (float)((double)(2 * j + 1) * half_c), cn, c1);
             sumC += c1;
-            sumN += (long long)(2 * j + 1) * cn;
+            sumN += (2 * j + 1) * cn;
         }
         int nL;
         double cL, s2L;
@@ -140,12 +140,12 @@ __device__ inline void fast_candidates(const FastLds &Q, int n, int len, int Li,
             const double wd = (double)(n - k);
             const double half_t = wd / (2.0 * Ld);
             double sumCt = 0.0;
-            long long sumNt = 0;
+            int sumNt = 0;
             for (int j = 0; j < Li; ++j) {
                 fast_query(Q, (float)(kd + (double)(2 * j + 1) * half_t), cn, c1);
                 const int nt = cn - nL;
                 sumCt += (c1 - cL) - kd * (double)nt;
-                sumNt += (long long)(2 * j + 1) * nt;
+                sumNt += (2 * j + 1) * nt;
             }
             const int ntL = len - nL;
             const double ctL = (S1tot - cL) - kd * (double)ntL;
@@ -155,6 +155,38 @@ __device__ inline void fast_candidates(const FastLds &Q, int n, int len, int Li,
                    st * st * (Ld * Ld * (double)ntL - (double)sumNt);
         }
         row[k - 1] = (float)(sse > 0.0 ? sse : 0.0);
+    }
+}
+
+// A tile whose values crowd into a few buckets (many equal magnitudes) would
+// make every look-up walk a long bucket; it is evaluated element by element
+// instead, in binary32 with the chunked sums of the plain search kernel (all
+// lanes read the same LDS word, which is a broadcast).
+__device__ inline void fast_plain(const float *__restrict__ elems, int len, int n, int Li,
+                                  float *__restrict__ row)
+{
+    const float Lf = (float)Li;
+    for (int k = threadIdx.x + 1; k <= n; k += kFastWG) {
+        const float kf = (float)k;
+        const float nk = (float)(n - k);
+        const float rc = Lf / kf;
+        const float rt = (k < n) ? Lf / nk : 0.0f;
+        const float ct = -kf * rt;
+        const float stepc = kf / Lf, stept = nk / Lf;
+        float outer = 0.0f;
+        for (int cb = 0; cb < len; cb += kChunk) {
+            const int ce = (cb + kChunk < len) ? cb + kChunk : len;
+            float acc = 0.0f;
+            for (int i = cb; i < ce; ++i) {
+                const float u = elems[i];
+                const bool tail = u > kf;
+                const float t = tail ? __builtin_fmaf(u, rt, ct) : u * rc;
+                const float err = (t - __builtin_rintf(t)) * (tail ? stept : stepc);
+                acc = __builtin_fmaf(err, err, acc);
+            }
+            outer += acc;
+        }
+        row[k - 1] = outer;
     }
 }
 
@@ -170,6 +202,7 @@ __global__ __launch_bounds__(kFastWG) void k_fast(Tables tb, int n, int bits, in
     __shared__ float redm[kFastWaves];
     __shared__ int redbad[kFastWaves];
     __shared__ int wsum[kFastWaves];
+    __shared__ int wcrowd[kFastWaves];
     __shared__ double wsum1[kFastWaves], wsum2[kFastWaves];
 
     const int t = blockIdx.x;
@@ -226,7 +259,7 @@ __global__ __launch_bounds__(kFastWG) void k_fast(Tables tb, int n, int bits, in
     const bool usable = (m > 0.0f) && (m < __builtin_inff());
     const float nf = (float)n;
     int shift = 16;                        // T = 2048: 128 buckets per octave
-    for (int x = T; x < kFastTMax; x <<= 1) ++shift;
+    for (int x = T; x < 2048; x <<= 1) ++shift;
     const int base = (__float_as_int(nf) >> shift) - (T - 1);
 
     // units and histogram
@@ -246,10 +279,18 @@ __global__ __launch_bounds__(kFastWG) void k_fast(Tables tb, int n, int bits, in
     const int lo = tid * per < T ? tid * per : T;
     const int hi = lo + per < T ? lo + per : T;
     {
-        int sum = 0;
-        for (int i = lo; i < hi; ++i) sum += cnt[i];
+        // bucket 0 (zeros and near-zeros, e.g. pruned weights) only counts as
+        // crowded if the lowest boundary, half a centre step of k = 1, can fall in it
+        const float lowest = 0.5f / (float)((1 << (bits - 1)) - 1);
+        const int first = (fast_bucket(lowest, shift, base) == 0) ? 0 : 1;
+        int sum = 0, fullest = 0;
+        for (int i = lo; i < hi; ++i) {
+            sum += cnt[i];
+            if (i >= first && cnt[i] > fullest) fullest = cnt[i];
+        }
         const int incl = wave_scan_incl(sum);
-        if (lane == 63) wsum[wave] = incl;
+        fullest = (__ballot(fullest > kFastCrowd) != 0ull) ? 1 : 0;
+        if (lane == 63) { wsum[wave] = incl; wcrowd[wave] = fullest; }
         __syncthreads();
         int run = incl - sum;
         for (int i = 0; i < wave; ++i) run += wsum[i];
@@ -271,7 +312,13 @@ __global__ __launch_bounds__(kFastWG) void k_fast(Tables tb, int n, int bits, in
             elems[start[c] + atomicAdd(&cnt[c], 1)] = u;
         }
     }
+    int crowded = 0;
+    for (int i = 0; i < kFastWaves; ++i) crowded |= wcrowd[i];
     __syncthreads();
+    if (crowded) {
+        fast_plain(elems, len, n, (1 << (bits - 1)) - 1, sse32 + (long long)t * n);
+        return;
+    }
 
     // per-bucket sums and their exclusive prefix (binary64)
     {
