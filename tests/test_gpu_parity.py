@@ -134,6 +134,31 @@ def test_many_distributions(P, bits):
     run_both(P, w[:64].reshape(8, -1), bits, 257, synth.PER_CHANNEL, f"distributions long bits={bits}")
 
 
+def test_prefix_sum_path_corner_cases(P):
+    """Inputs chosen against the bucketed prefix-sum evaluator of the fast search:
+    equal magnitudes (one crowded bucket), pruned weights (mostly zeros), values
+    spread over many octaves, lengths around the switch-over, many candidates."""
+    rng = np.random.default_rng(99)
+    K = 2000
+    rows = [np.full(K, 0.37) * np.sign(rng.standard_normal(K)),
+            rng.standard_normal(K) * (rng.random(K) < 0.03),
+            np.exp(rng.uniform(-30, 0, K)) * np.sign(rng.standard_normal(K)),
+            np.concatenate([np.full(K - 5, 1e-3), [1.0, 0.5, 0.25, 0.125, 0.0625]]),
+            np.round(rng.standard_normal(K) * 2) / 2,
+            rng.standard_normal(K)]
+    w = np.stack(rows).astype(np.float32)
+    for bits in (2, 3, 4):
+        run_both(P, w, bits, 500, synth.PER_CHANNEL, f"prefix-sum corners bits={bits}")
+    run_both(P, w, 4, 65535, synth.PER_CHANNEL, "prefix-sum corners n=65535")
+    run_both(P, w, 3, 777, synth.PER_TENSOR, "prefix-sum corners per-tensor")
+    for K in (303, 304, 305, 511, 513):
+        wk = rng.laplace(0, 0.05, size=(6, K)).astype(np.float32)
+        run_both(P, wk, 4, 200, synth.PER_CHANNEL, f"prefix-sum switch-over K={K}")
+    big = rng.standard_normal((2, 8192)).astype(np.float32)
+    run_both(P, big, 8, 300, synth.PER_CHANNEL, "prefix-sum bits=8")
+    run_both(P, big, 6, 300, synth.PER_CHANNEL, "prefix-sum bits=6")
+
+
 # ------------------------------------------------------------------ degenerate
 def test_degenerate_groups(P):
     w = np.zeros((8, 100), np.float32)
