@@ -386,6 +386,72 @@ int pwlq_ref_mse(const float *w, int64_t C, int64_t K, int bits, int mode, const
     return REF_OK;
 }
 
+/*
+ * Section 4: inner products of uniformly quantized activations with PWLQ
+ * weights on integer arithmetic.  Activations are X_hat = s_x X_q + z_x (Eq.1,
+ * 8-bit, one scale and offset per call), weights are stored as b-bit
+ * sign-magnitude codes plus the region bit.  With the signed code
+ * w_q = sign * (piece code) and sigma = sign for a tail weight, the two paths
+ * of Section 4 are
+ *     P1 = C2 <X_q, W_q1>_R1 + C3,                       (centre, offset 0)
+ *     P2 = C4 <X_q, W_q2>_R2 + C5 <X_q, sigma>_R2 + C6,  (tail, offset p)
+ * with C2 = s_x s_1, C4 = s_x s_2, C5 = s_x p and the constants
+ * C3 = z_x s_1 sum_R1 w_q,  C6 = z_x (s_2 sum_R2 w_q + p sum_R2 sigma).
+ * (The paper writes <X_q, I>_R2 for magnitudes; on signed weights the offset p
+ * carries the weight's sign, Eq.3.)  Three integer accumulators per output,
+ * as Section 4 counts them.  s_1 = fl32(p/L), s_2 = fl32(fl32(m-p)/L) are the
+ * quantizer's own binary32 steps; everything after the integer sums is
+ * binary64.
+ *
+ * xq [M,K] int8; codes, flags [N,K] one byte each (as pwlq_ref_quantize writes
+ * them); p, m per output channel n.  acc (optional) [3][M][N]: the integer
+ * sums <X_q,W_q1>_R1, <X_q,W_q2>_R2, <X_q,sigma>_R2.  y [M][N] = P1 + P2.
+ */
+int pwlq_ref_linear(const int8_t *xq, int64_t M, int64_t K, float s_x, float z_x,
+                    const uint8_t *codes, const uint8_t *flags, int64_t N, int bits,
+                    const float *p, const float *m, int64_t *acc, double *y)
+{
+    if (!xq || !codes || !flags || !p || !m || !y) return REF_ENULL;
+    if (M < 1 || K < 1 || N < 1 || bits < 2 || bits > 8) return REF_EINVAL;
+    const int sign_bit = 1 << (bits - 1);
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        pieces q = make_pieces(m[n], p[n], bits);
+        const uint8_t *c = codes + n * K, *f = flags + n * K;
+        /* constants of the channel */
+        int64_t sum1 = 0, sum2 = 0, sum3 = 0;
+        for (int64_t k = 0; k < K; ++k) {
+            int mag = c[k] & (sign_bit - 1);
+            int sg = (c[k] & sign_bit) ? -1 : 1;
+            if (f[k]) { sum2 += sg * mag; sum3 += sg; }
+            else sum1 += sg * mag;
+        }
+        double C2 = (double)s_x * (double)q.s1, C4 = (double)s_x * (double)q.s2;
+        double C5 = (double)s_x * (double)q.p;
+        double C3 = (double)z_x * (double)q.s1 * (double)sum1;
+        double C6 = (double)z_x * ((double)q.s2 * (double)sum2 + (double)q.p * (double)sum3);
+        for (int64_t i = 0; i < M; ++i) {
+            const int8_t *x = xq + i * K;
+            int64_t a1 = 0, a2 = 0, a3 = 0;
+            for (int64_t k = 0; k < K; ++k) {
+                int mag = c[k] & (sign_bit - 1);
+                int sg = (c[k] & sign_bit) ? -1 : 1;
+                if (f[k]) { a2 += (int64_t)x[k] * (sg * mag); a3 += (int64_t)x[k] * sg; }
+                else a1 += (int64_t)x[k] * (sg * mag);
+            }
+            if (acc) {
+                acc[(0 * M + i) * N + n] = a1;
+                acc[(1 * M + i) * N + n] = a2;
+                acc[(2 * M + i) * N + n] = a3;
+            }
+            double P1 = C2 * (double)a1 + C3;
+            double P2 = C4 * (double)a2 + C5 * (double)a3 + C6;
+            y[i * N + n] = P1 + P2;
+        }
+    }
+    return REF_OK;
+}
+
 int pwlq_ref_num_threads(void)
 {
 #ifdef _OPENMP

@@ -61,8 +61,38 @@ def lib() -> ctypes.CDLL:
         L.pwlq_ref_mse.restype = ctypes.c_int
         L.pwlq_ref_mse.argtypes = [fp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
                                    fp, fp, dp]
+        L.pwlq_ref_linear.restype = ctypes.c_int
+        L.pwlq_ref_linear.argtypes = [ctypes.POINTER(ctypes.c_int8), ctypes.c_int64, ctypes.c_int64,
+                                      ctypes.c_float, ctypes.c_float, bp, bp, ctypes.c_int64,
+                                      ctypes.c_int, fp, fp, ctypes.POINTER(ctypes.c_int64), dp]
         _lib = L
     return _lib
+
+
+def linear(xq: np.ndarray, s_x: float, z_x: float, codes: np.ndarray, flags: np.ndarray, bits: int,
+           p: np.ndarray, m: np.ndarray, want_acc: bool = False):
+    """Section 4's integer inner products.  xq int8 [M, K]; codes, flags uint8 [N, K]
+    (one byte each); p, m float32 [N].  Returns y float64 [M, N] (and the three
+    integer sums int64 [3, M, N])."""
+    xq = np.ascontiguousarray(xq, dtype=np.int8)
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    flags = np.ascontiguousarray(flags, dtype=np.uint8)
+    p = np.ascontiguousarray(p, dtype=np.float32)
+    m = np.ascontiguousarray(m, dtype=np.float32)
+    M, K = xq.shape
+    N = codes.shape[0]
+    if codes.shape != (N, K) or flags.shape != (N, K) or p.shape != (N,) or m.shape != (N,):
+        raise ValueError("shape mismatch")
+    y = np.empty((M, N), np.float64)
+    acc = np.empty((3, M, N), np.int64) if want_acc else None
+    rc = lib().pwlq_ref_linear(_ptr(xq, ctypes.c_int8), M, K, s_x, z_x,
+                               _ptr(codes, ctypes.c_uint8), _ptr(flags, ctypes.c_uint8), N, bits,
+                               _ptr(p, ctypes.c_float), _ptr(m, ctypes.c_float),
+                               _ptr(acc, ctypes.c_int64) if want_acc else None,
+                               _ptr(y, ctypes.c_double))
+    if rc != 0:
+        raise ValueError(f"pwlq_ref_linear status {rc}")
+    return (y, acc) if want_acc else y
 
 
 GAUSS_FIT, GAUSS_SOLVE, LAPLACE_SOLVE = 0, 1, 2
