@@ -210,6 +210,34 @@ int pwlq_mse_list(const pwlq_tensor_desc *desc, int n_tensors, int bits, int mod
                   const float *m, double *mse, void *workspace, size_t workspace_bytes,
                   void *stream);
 
+/*
+ * Consumer of the packed format: Y = X_hat W_hat^T on integer arithmetic
+ * (Section 4).  Activations are uniformly quantized 8-bit values (Eq.1) with
+ * one step and one offset for the call, X_hat = s_x * xq + z_x, xq int8 [M, K]
+ * row-major.  Weights [N, K] are per-output-channel PWLQ weights in the packed
+ * format of pwlq_quantize_packed (one tensor: element n*K + k of the streams),
+ * with p and m the N per-channel parameters they were quantized with.  For
+ * every output the three integer sums of Section 4 are formed on the int8
+ * matrix cores,
+ *     A1 = <xq, w_q>_R1,  A2 = <xq, w_q>_R2,  A3 = <xq, sigma>_R2
+ * (w_q the signed code, sigma the sign of a tail weight, which the offset p
+ * carries), and combined in binary32:
+ *     y = s_x (s1 A1 + s2 A2 + p A3) + z_x (s1 sum_R1 w_q + s2 sum_R2 w_q + p sum_R2 sigma)
+ * with s1 = p/L, s2 = (m - p)/L, L = 2^(bits-1) - 1: the constants C2..C6 of
+ * Section 4.
+ *   y    device [M, N] binary32, row-major
+ *   acc  device [3, M, N] int32 receiving A1, A2, A3, or NULL
+ * Requirements: K a multiple of 64; xq and packed_codes 16-byte aligned,
+ * packed_flags 2-byte aligned; K * 128 * L below 2^31.  Workspace: device,
+ * 256-byte aligned, pwlq_linear_workspace_bytes(N) bytes.
+ */
+size_t pwlq_linear_workspace_bytes(int64_t N);
+
+int pwlq_linear_i8(const int8_t *xq, int64_t M, int64_t K, float s_x, float z_x,
+                   const uint8_t *packed_codes, const uint8_t *packed_flags, int64_t N, int bits,
+                   const float *p, const float *m, float *y, int32_t *acc, void *workspace,
+                   size_t workspace_bytes, void *stream);
+
 /* Text of the calling thread's last non-OK status ("" if none).  The storage
  * is thread-local and owned by the library. */
 const char *pwlq_last_error(void);
@@ -221,15 +249,16 @@ void pwlq_last_search_shape(int64_t *n_tiles, int64_t *n_groups, int64_t *n_unit
 /* Benchmark aid.  With profiling enabled every search / quantize call records
  * HIP events on its own stream right before and after its dominant kernel
  * (role 0: the candidate-evaluation kernel of a search; role 1: the quantize
- * kernel; role 2: the prefix-sum evaluation kernel of a fast search).  pwlq_profile_last_ms waits for the later event of the most recent
+ * kernel; role 2: the prefix-sum evaluation kernel of a fast search; role 3: the
+ * integer inner-product kernel).  pwlq_profile_last_ms waits for the later event of the most recent
  * call and returns the kernel's duration in milliseconds, or -1 if none was
  * recorded.  Process-wide, not thread-safe; off by default. */
 void pwlq_profile_enable(int on);
 double pwlq_profile_last_ms(int role);
 
 /* Name of the library's kernels as they appear in a kernel trace, by role:
- * 0 search (dominant), 1 quantize, 2 prefix-sum evaluation.  Returns NULL for
- * other roles. */
+ * 0 search (dominant), 1 quantize, 2 prefix-sum evaluation, 3 integer inner
+ * product.  Returns NULL for other roles. */
 const char *pwlq_kernel_name(int role);
 
 #ifdef __cplusplus

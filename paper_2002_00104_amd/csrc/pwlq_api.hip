@@ -238,9 +238,9 @@ int launch_status(const char *what)
 
 // Optional event timing of the dominant kernels (benchmarks only).
 bool g_profile = false;
-hipEvent_t g_ev[6];
+hipEvent_t g_ev[8];
 bool g_ev_made = false;
-bool g_ev_valid[3] = {false, false, false};
+bool g_ev_valid[4] = {false, false, false, false};
 
 void profile_mark(int idx, hipStream_t stream)
 {
@@ -461,9 +461,62 @@ int run_mse(const pwlq_tensor_desc *desc, int n_tensors, int bits, int mode, con
     return launch_status("mse launch");
 }
 
+int run_linear(const int8_t *xq, int64_t M, int64_t K, float s_x, float z_x,
+               const uint8_t *packed_codes, const uint8_t *packed_flags, int64_t N, int bits,
+               const float *p, const float *m, float *y, int32_t *acc, void *workspace,
+               size_t workspace_bytes, void *stream_v)
+{
+    int rc = check_common(bits, PWLQ_PER_CHANNEL);
+    if (rc) return rc;
+    if (!xq || !packed_codes || !packed_flags || !p || !m || !y)
+        return fail(PWLQ_ENULL, "an input or output pointer is NULL");
+    if (M < 1 || N < 1 || K < 1) return fail(PWLQ_EINVAL, "M=%lld N=%lld K=%lld must be >= 1",
+                                             (long long)M, (long long)N, (long long)K);
+    if (K % kLinBK != 0) return fail(PWLQ_EINVAL, "K=%lld is not a multiple of %d", (long long)K, kLinBK);
+    if (M > (1LL << 31) / 4 || N > (1LL << 31) / 4 || K > (1LL << 24))
+        return fail(PWLQ_EINVAL, "matrix too large");
+    if ((((uintptr_t)xq) | ((uintptr_t)packed_codes)) & 15)
+        return fail(PWLQ_EINVAL, "xq and packed_codes must be 16-byte aligned");
+    if (((uintptr_t)packed_flags) & 1) return fail(PWLQ_EINVAL, "packed_flags must be 2-byte aligned");
+    const size_t need = align_up(sizeof(float) * (size_t)N, 256);
+    if (!workspace) return fail(PWLQ_EWORKSPACE, "workspace is NULL (%zu bytes needed)", need);
+    if (((uintptr_t)workspace & 255) != 0) return fail(PWLQ_EWORKSPACE, "workspace is not 256-byte aligned");
+    if (workspace_bytes < need)
+        return fail(PWLQ_EWORKSPACE, "workspace holds %zu bytes, %zu needed", workspace_bytes, need);
+    const long long tiles_m = (M + kLinBM - 1) / kLinBM, tiles_n = (N + kLinBN - 1) / kLinBN;
+    const long long tn_per_xcd = (tiles_n + 7) / 8;
+    const long long wgs = 8 * tn_per_xcd * tiles_m;
+    if (wgs > 0x7fffffffLL) return fail(PWLQ_EINVAL, "grid too large");
+    hipStream_t stream = (hipStream_t)stream_v;
+    float *wconst = (float *)workspace;
+    k_linear_wsum<<<(unsigned)((N + kLinWG / 64 - 1) / (kLinWG / 64)), kLinWG, 0, stream>>>(
+        packed_codes, packed_flags, N, K, bits, p, m, wconst);
+    profile_mark(6, stream);
+    k_linear<<<(unsigned)wgs, kLinWG, 0, stream>>>(xq, M, K, s_x, z_x, packed_codes, packed_flags, N,
+                                                  bits, p, m, wconst, y, acc, (int)tiles_m,
+                                                  (int)tiles_n, (int)tn_per_xcd);
+    profile_mark(7, stream);
+    return launch_status("linear launch");
+}
+
 } // namespace
 
 extern "C" {
+
+size_t pwlq_linear_workspace_bytes(int64_t N)
+{
+    if (N < 1) return 0;
+    return align_up(sizeof(float) * (size_t)N, 256);
+}
+
+int pwlq_linear_i8(const int8_t *xq, int64_t M, int64_t K, float s_x, float z_x,
+                   const uint8_t *packed_codes, const uint8_t *packed_flags, int64_t N, int bits,
+                   const float *p, const float *m, float *y, int32_t *acc, void *workspace,
+                   size_t workspace_bytes, void *stream)
+{
+    return run_linear(xq, M, K, s_x, z_x, packed_codes, packed_flags, N, bits, p, m, y, acc,
+                      workspace, workspace_bytes, stream);
+}
 
 size_t pwlq_select_list_workspace_bytes(const pwlq_tensor_desc *desc, int n_tensors, int mode)
 {
@@ -636,7 +689,7 @@ void pwlq_profile_enable(int on) { g_profile = on != 0; }
 
 double pwlq_profile_last_ms(int role)
 {
-    if (role < 0 || role > 2 || !g_ev_made || !g_ev_valid[role]) return -1.0;
+    if (role < 0 || role > 3 || !g_ev_made || !g_ev_valid[role]) return -1.0;
     float ms = -1.0f;
     if (hipEventSynchronize(g_ev[2 * role + 1]) != hipSuccess) return -1.0;
     if (hipEventElapsedTime(&ms, g_ev[2 * role], g_ev[2 * role + 1]) != hipSuccess) return -1.0;
@@ -655,6 +708,7 @@ const char *pwlq_kernel_name(int role)
     if (role == 0) return "k_search";
     if (role == 1) return "k_emit";
     if (role == 2) return "k_fast";
+    if (role == 3) return "k_linear";
     return nullptr;
 }
 

@@ -26,3 +26,4 @@
 #include "pwlq_emit.h"
 #include "pwlq_select.h"
 #include "pwlq_fast.h"
+#include "pwlq_linear.h"

@@ -29,6 +29,7 @@ EXPORTS = (
     "pwlq_select_workspace_bytes", "pwlq_select_list_workspace_bytes", "pwlq_select_analytic",
     "pwlq_select_analytic_list",
     "pwlq_mse_workspace_bytes", "pwlq_mse_list_workspace_bytes", "pwlq_mse", "pwlq_mse_list",
+    "pwlq_linear_workspace_bytes", "pwlq_linear_i8",
     "pwlq_last_error", "pwlq_last_search_shape", "pwlq_profile_enable",
     "pwlq_profile_last_ms", "pwlq_kernel_name",
 )
@@ -96,6 +97,11 @@ def _load() -> ctypes.CDLL:
     lib.pwlq_mse.argtypes = [vp, i64, i64, ci, ci, vp, vp, vp, vp, sz, vp]
     lib.pwlq_mse_list.restype = ci
     lib.pwlq_mse_list.argtypes = [dp, ci, ci, ci, vp, vp, vp, vp, sz, vp]
+    lib.pwlq_linear_workspace_bytes.restype = sz
+    lib.pwlq_linear_workspace_bytes.argtypes = [i64]
+    lib.pwlq_linear_i8.restype = ci
+    lib.pwlq_linear_i8.argtypes = [vp, i64, i64, ctypes.c_float, ctypes.c_float, vp, vp, i64, ci,
+                                   vp, vp, vp, vp, vp, sz, vp]
     lib.pwlq_last_error.restype = ctypes.c_char_p
     lib.pwlq_last_error.argtypes = []
     lib.pwlq_last_search_shape.restype = None
@@ -393,6 +399,27 @@ def mse_list(tl: "TensorList", bits: int, p: torch.Tensor, m: torch.Tensor,
     _check(lib.pwlq_mse_list(tl.desc, len(tl), bits, tl.mode, p.data_ptr(), m.data_ptr(),
                              out.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream()))
     return out
+
+
+def linear_i8(xq: torch.Tensor, s_x: float, z_x: float, packed_codes: torch.Tensor,
+              packed_flags: torch.Tensor, N: int, bits: int, p: torch.Tensor, m: torch.Tensor,
+              want_acc: bool = False, workspace: Optional[torch.Tensor] = None, out=None):
+    """pwlq_linear_i8.  xq int8 [M, K] (device); packed streams of a [N, K] weight.
+    Returns (y f32 [M, N], acc i32 [3, M, N] or None)."""
+    if not (xq.is_cuda and xq.dtype == torch.int8 and xq.is_contiguous() and xq.dim() == 2):
+        raise ValueError("xq must be a contiguous int8 [M, K] tensor on the GPU")
+    M, K = xq.shape
+    if workspace is None:
+        workspace = _workspace(lib.pwlq_linear_workspace_bytes(N), xq.device)
+    if out is None:
+        out = (torch.empty((M, N), dtype=torch.float32, device=xq.device),
+               torch.empty((3, M, N), dtype=torch.int32, device=xq.device) if want_acc else None)
+    y, acc = out
+    _check(lib.pwlq_linear_i8(xq.data_ptr(), M, K, s_x, z_x, packed_codes.data_ptr(),
+                              packed_flags.data_ptr(), N, bits, p.data_ptr(), m.data_ptr(),
+                              y.data_ptr(), acc.data_ptr() if acc is not None else None,
+                              workspace.data_ptr(), workspace.numel(), _stream()))
+    return y, acc
 
 
 def profile_enable(on: bool) -> None:
