@@ -57,6 +57,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", type=int, default=2, help="1..5 (default 2: ResNet-50 shapes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-linear", action="store_true",
+                    help="skip the timing of the integer inner-product kernel")
     ap.add_argument("--only-k", type=int, default=0,
                     help="keep only the tensors whose rows have this many elements "
                          "(e.g. 9: the depthwise channels of workload 3)")
@@ -270,6 +272,48 @@ def main() -> int:
             "mse_over_grid_optimum_max": float(ratio.max()),
             "total_sse_over_grid_optimum": float(
                 (mse_out[ok] * tl.group_counts(ok)).sum() / (best[ok] * tl.group_counts(ok)).sum()),
+        }
+
+    # Consumer of the packed format (Section 4): int8 activations [4096, 4096]
+    # times a PWLQ-quantized [4096, 4096] linear weight (b = 4, Laplacian values of
+    # workload 5's kind), three integer accumulators per output on the int8 matrix
+    # cores.  `achieved` counts the multiply-adds the matrix cores execute (three
+    # planes); `algorithmic` counts one multiply-add per (row, channel, k).
+    if not args.no_linear:
+        Ml, Kl, Nl, bl = 4096, 4096, 4096, 4
+        gen = torch.Generator(device="cuda").manual_seed(7)
+        u01 = torch.rand((Nl, Kl), generator=gen, device="cuda") - 0.5
+        wlin = (-0.02 * torch.sign(u01) * torch.log1p(-2.0 * u01.abs())).contiguous()   # Laplace(0, 0.02)
+        sl = pwlq.search(wlin, bl, 100, fast=True)
+        pc, pf, _ = pwlq.quantize_packed(wlin, bl, sl["p_star"], sl["m"], want_w_hat=False)
+        xq = torch.randint(-128, 128, (Ml, Kl), generator=gen, device="cuda", dtype=torch.int8)
+        ws_lin = torch.empty(max(256, pwlq.lib.pwlq_linear_workspace_bytes(Nl)), dtype=torch.uint8,
+                             device="cuda")
+        lout = (torch.empty((Ml, Nl), dtype=torch.float32, device="cuda"), None)
+        for _ in range(2):
+            pwlq.linear_i8(xq, 0.02, -0.5, pc, pf, Nl, bl, sl["p_star"], sl["m"], workspace=ws_lin,
+                           out=lout)
+        torch.cuda.synchronize()
+        pwlq.profile_enable(True)
+        lin_ms = []
+        for _ in range(reps):
+            pwlq.linear_i8(xq, 0.02, -0.5, pc, pf, Nl, bl, sl["p_star"], sl["m"], workspace=ws_lin,
+                           out=lout)
+            lin_ms.append(pwlq.profile_last_ms(3))
+        pwlq.profile_enable(False)
+        lm = float(np.mean(lin_ms))
+        ops = 2.0 * Ml * Nl * Kl
+        result["linear_i8"] = {
+            "kernel": pwlq.kernel_name(3),
+            "shape": f"xq [{Ml},{Kl}] int8 x packed PWLQ weight [{Nl},{Kl}], b={bl}",
+            "kernel_ms": lm,
+            "bound": "mfma",
+            "achieved": 3.0 * ops / (lm * 1e-3) / 1e12,
+            "algorithmic": ops / (lm * 1e-3) / 1e12,
+            "peak": 5000.0,
+            "unit": "TOP/s int8 (dense MFMA)",
+            "frac": 3.0 * ops / (lm * 1e-3) / 5e15,
+            "weight_bytes_per_element": (bl + 1) / 8.0,
         }
 
     if not args.no_cpu_baseline:

@@ -489,13 +489,28 @@ int run_linear(const int8_t *xq, int64_t M, int64_t K, float s_x, float z_x,
     if (wgs > 0x7fffffffLL) return fail(PWLQ_EINVAL, "grid too large");
     hipStream_t stream = (hipStream_t)stream_v;
     float *wconst = (float *)workspace;
-    k_linear_wsum<<<(unsigned)((N + kLinWG / 64 - 1) / (kLinWG / 64)), kLinWG, 0, stream>>>(
-        packed_codes, packed_flags, N, K, bits, p, m, wconst);
-    profile_mark(6, stream);
-    k_linear<<<(unsigned)wgs, kLinWG, 0, stream>>>(xq, M, K, s_x, z_x, packed_codes, packed_flags, N,
-                                                  bits, p, m, wconst, y, acc, (int)tiles_m,
-                                                  (int)tiles_n, (int)tn_per_xcd);
-    profile_mark(7, stream);
+    const unsigned wsum_wgs = (unsigned)((N + kLinWG / 64 - 1) / (kLinWG / 64));
+#define PWLQ_LINEAR_CASE(B)                                                                       \
+    case B:                                                                                        \
+        k_linear_wsum<B><<<wsum_wgs, kLinWG, 0, stream>>>(packed_codes, packed_flags, N, K, p, m,  \
+                                                          wconst);                                 \
+        profile_mark(6, stream);                                                                   \
+        k_linear<B><<<(unsigned)wgs, kLinWG, 0, stream>>>(xq, M, K, s_x, z_x, packed_codes,        \
+                                                         packed_flags, N, p, m, wconst, y, acc,    \
+                                                         (int)tiles_m, (int)tiles_n,               \
+                                                         (int)tn_per_xcd);                         \
+        profile_mark(7, stream);                                                                   \
+        break;
+    switch (bits) {
+        PWLQ_LINEAR_CASE(2)
+        PWLQ_LINEAR_CASE(3)
+        PWLQ_LINEAR_CASE(4)
+        PWLQ_LINEAR_CASE(5)
+        PWLQ_LINEAR_CASE(6)
+        PWLQ_LINEAR_CASE(7)
+        PWLQ_LINEAR_CASE(8)
+    }
+#undef PWLQ_LINEAR_CASE
     return launch_status("linear launch");
 }
 

@@ -21,59 +21,100 @@ namespace pwlq {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-constexpr int kLinBM = 128;       // activation rows per workgroup
+#ifndef LIN_MT
+#define LIN_MT 2
+#endif
+#ifndef LIN_WM
+#define LIN_WM 2
+#endif
+constexpr int kLinMT = LIN_MT;     // 32-row tiles per wavefront
+constexpr int kLinWM = LIN_WM;     // wavefronts along the rows; 2 along the channels
+constexpr int kLinBM = kLinWM * 32 * kLinMT;   // activation rows per workgroup
 constexpr int kLinBN = 64;        // output channels per workgroup
 constexpr int kLinBK = 64;        // reduction elements per step
-constexpr int kLinStride = 80;    // bytes per LDS row: 64 + 16 keeps 16-byte reads off the same banks
-constexpr int kLinWG = 256;       // 4 wavefronts, 2 (rows) x 2 (channels), each 64 x 32 outputs
+constexpr int kLinStride = 64;    // bytes per LDS row; the four 16-byte chunks of a row are swizzled
+constexpr int kLinWG = 128 * kLinWM;   // wavefronts kLinWM (rows) x 2 (channels), each 32*kLinMT x 32 outputs
+
+// LDS rows hold 64 reduction bytes as four 16-byte chunks; chunk c of row r is
+// stored at position c ^ swz(r).  With swz(r) = ((r>>1) + (r>>3)) & 3 the 16-byte
+// reads of the matrix-core fragments (consecutive lanes = consecutive rows, same
+// chunk) and the 16-byte writes of the staging threads (consecutive lanes = the
+// four chunks of consecutive rows) each touch every bank once, for 32 and for
+// 64 banks, without padding.
+__device__ inline int lin_swz(int row) { return ((row >> 1) + (row >> 3)) & 3; }
 
 // 16 consecutive b-bit codes of a stream (sign-magnitude: bit b-1 is the sign)
-// starting at element index e0 (a multiple of 16), returned as 16 bytes, one
-// code per byte, in order.  The 2b bytes start 2-byte aligned.
-__device__ inline void load_codes16(const uint8_t *__restrict__ stream, long long e0, int bits,
-                                    uint32_t (&out)[4])
+// starting at element index e0 (a multiple of 16) occupy 2b bytes that start
+// 2-byte aligned (4-byte aligned for even b, 8 for b = 4, 16 for b = 8).
+// load_raw16 only issues the loads; unpack16 turns the raw bytes into 16 bytes,
+// one code per byte, in order.  Keeping the two apart lets the loads of a later
+// step fly while the matrix cores work on the current one.
+template <int kBits>
+struct RawCodes {
+    uint32_t w[(2 * kBits + 3) / 4];
+};
+
+template <int kBits>
+__device__ inline void load_raw16(const uint8_t *__restrict__ stream, long long e0,
+                                  RawCodes<kBits> &raw)
 {
-    const uint8_t *src = stream + (e0 >> 4) * (2 * bits);
-    if (bits == 4) {
-        const uint2 v = *reinterpret_cast<const uint2 *>(src);      // 8-byte aligned
-        const uint32_t w[2] = {v.x, v.y};
+    const uint8_t *src = stream + (e0 >> 4) * (2 * kBits);
+    if (kBits == 4) {
+        const uint2 v = *reinterpret_cast<const uint2 *>(src);
+        raw.w[0] = v.x;
+        raw.w[1] = v.y;
+    } else if (kBits == 8) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(src);
+        raw.w[0] = v.x; raw.w[1] = v.y; raw.w[2] = v.z; raw.w[3] = v.w;
+    } else if (kBits % 2 == 0) {
+#pragma unroll
+        for (int i = 0; i < kBits / 2; ++i) raw.w[i] = reinterpret_cast<const uint32_t *>(src)[i];
+    } else {
+        const uint16_t *s16 = reinterpret_cast<const uint16_t *>(src);
+#pragma unroll
+        for (int i = 0; i < (2 * kBits + 3) / 4; ++i) raw.w[i] = 0;
+#pragma unroll
+        for (int i = 0; i < kBits; ++i) raw.w[i / 2] |= (uint32_t)s16[i] << (16 * (i & 1));
+    }
+}
+
+template <int kBits>
+__device__ inline void zero_raw16(RawCodes<kBits> &raw)
+{
+#pragma unroll
+    for (int i = 0; i < (2 * kBits + 3) / 4; ++i) raw.w[i] = 0;
+}
+
+template <int kBits>
+__device__ inline void unpack16(const RawCodes<kBits> &raw, uint32_t (&out)[4])
+{
+    if (kBits == 4) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            const uint32_t ev = w[h] & 0x0f0f0f0fu;          // elements 0,2,4,6 of this half
-            const uint32_t od = (w[h] >> 4) & 0x0f0f0f0fu;   // elements 1,3,5,7
+            const uint32_t ev = raw.w[h] & 0x0f0f0f0fu;          // elements 0,2,4,6 of this half
+            const uint32_t od = (raw.w[h] >> 4) & 0x0f0f0f0fu;   // elements 1,3,5,7
             // interleave bytes: (e0,o0,e1,o1) and (e2,o2,e3,o3)
             out[2 * h] = __builtin_amdgcn_perm(od, ev, 0x05010400u);
             out[2 * h + 1] = __builtin_amdgcn_perm(od, ev, 0x07030602u);
         }
-        return;
-    }
-    if (bits == 8) {
-        const uint4 v = *reinterpret_cast<const uint4 *>(src);      // 16-byte aligned
-        out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
-        return;
-    }
-    // any other width: gather the 2b bytes into a 128-bit window, then shift
-    unsigned long long lo = 0, hi = 0;
-    const uint16_t *s16 = reinterpret_cast<const uint16_t *>(src);
-    for (int i = 0; i < bits; ++i) {
-        const unsigned long long h = s16[i];
-        if (i < 4) lo |= h << (16 * i);
-        else hi |= h << (16 * (i - 4));
-    }
-    const uint32_t mask = (1u << bits) - 1u;
+    } else if (kBits == 8) {
 #pragma unroll
-    for (int wd = 0; wd < 4; ++wd) {
-        uint32_t word = 0;
+        for (int i = 0; i < 4; ++i) out[i] = raw.w[i];
+    } else {
+        constexpr uint32_t mask = (1u << kBits) - 1u;
 #pragma unroll
-        for (int x = 0; x < 4; ++x) {
-            const int pos = (wd * 4 + x) * bits;
-            unsigned long long v;
-            if (pos >= 64) v = hi >> (pos - 64);
-            else if (pos == 0) v = lo;
-            else v = (lo >> pos) | (hi << (64 - pos));
-            word |= ((uint32_t)v & mask) << (8 * x);
+        for (int wd = 0; wd < 4; ++wd) {
+            uint32_t word = 0;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                const int pos = (wd * 4 + x) * kBits;       // compile-time after unrolling
+                const int wi = pos >> 5, sh = pos & 31;
+                uint32_t v = raw.w[wi] >> sh;
+                if (sh + kBits > 32) v |= raw.w[wi + 1] << (32 - sh);
+                word |= (v & mask) << (8 * x);
+            }
+            out[wd] = word;
         }
-        out[wd] = word;
     }
 }
 
@@ -85,10 +126,11 @@ __device__ inline void planes4(uint32_t codes, uint32_t f, int bits, uint32_t &w
     const uint32_t magmask = ((1u << (bits - 1)) - 1u) * 0x01010101u;
     const uint32_t mag = codes & magmask;
     const uint32_t sgn = (codes >> (bits - 1)) & 0x01010101u;
-    const uint32_t smask = sgn * 0xffu;                                 // 0xff in bytes of negative codes
+    const uint32_t smask = (sgn << 8) - sgn;                            // 0xff in bytes of negative codes
     const uint32_t neg = (0x80808080u - mag) ^ 0x80808080u;            // -mag per byte (mag <= 127)
     const uint32_t val = (neg & smask) | (mag & ~smask);
-    const uint32_t fm = (((f & 0xfu) * 0x00204081u) & 0x01010101u) * 0xffu;   // 0xff in tail bytes
+    const uint32_t f01 = ((f & 0xfu) * 0x00204081u) & 0x01010101u;     // region bit of each byte
+    const uint32_t fm = (f01 << 8) - f01;                               // 0xff in tail bytes
     w1 = val & ~fm;
     w2 = val & fm;
     w3 = (smask | 0x01010101u) & fm;
@@ -104,9 +146,10 @@ __device__ inline int sum_bytes(uint32_t w)
            (int)(int8_t)((w >> 16) & 0xff) + (int)(int8_t)(w >> 24);
 }
 
+template <int kBits>
 __global__ __launch_bounds__(kLinWG) void k_linear_wsum(const uint8_t *__restrict__ pcodes,
                                                         const uint8_t *__restrict__ pflags,
-                                                        long long N, long long K, int bits,
+                                                        long long N, long long K,
                                                         const float *__restrict__ p,
                                                         const float *__restrict__ m,
                                                         float *__restrict__ wconst)
@@ -117,13 +160,15 @@ __global__ __launch_bounds__(kLinWG) void k_linear_wsum(const uint8_t *__restric
     int b1 = 0, b2 = 0, b3 = 0;
     for (long long k0 = 16LL * lane; k0 < K; k0 += 16 * 64) {
         const long long e0 = n * K + k0;
+        RawCodes<kBits> raw;
         uint32_t c[4];
-        load_codes16(pcodes, e0, bits, c);
+        load_raw16<kBits>(pcodes, e0, raw);
+        unpack16<kBits>(raw, c);
         const uint32_t f = *reinterpret_cast<const uint16_t *>(pflags + (e0 >> 3));
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
             uint32_t w1, w2, w3;
-            planes4(c[x], f >> (4 * x), bits, w1, w2, w3);
+            planes4(c[x], f >> (4 * x), kBits, w1, w2, w3);
             b1 += sum_bytes(w1);
             b2 += sum_bytes(w2);
             b3 += sum_bytes(w3);
@@ -135,7 +180,7 @@ __global__ __launch_bounds__(kLinWG) void k_linear_wsum(const uint8_t *__restric
         b3 += __shfl_xor(b3, off, 64);
     }
     if (lane == 0) {
-        const float Lf = (float)((1 << (bits - 1)) - 1);
+        const float Lf = (float)((1 << (kBits - 1)) - 1);
         const float pn = p[n], mn = m[n];
         const float s1 = pn / Lf;
         const float width = mn - pn;
@@ -145,69 +190,119 @@ __global__ __launch_bounds__(kLinWG) void k_linear_wsum(const uint8_t *__restric
 }
 
 // -------------------------------------------------------------------- linear
+constexpr int kLinAVec = kLinBM * kLinBK / 16 / kLinWG;   // 16-byte activation loads per thread
+
+template <int kBits>
 struct LinStage {
-    v4i a0, a1;            // 32 activation bytes of one row
-    uint32_t codes[4];     // 16 weight codes, one per byte
+    v4i a[kLinAVec];       // activation bytes: vector v of thread t is piece t + v*kLinWG of the tile
+    RawCodes<kBits> codes; // 16 packed weight codes
     uint32_t flags;        // their 16 region bits
 };
 
-__device__ inline void lin_load(LinStage &st, const int8_t *__restrict__ xq, long long M,
+// Issues the loads of one reduction step and nothing else.  Rows past M and
+// channels past N read the last valid row / channel instead (their products are
+// never written), so no load sits under a branch and the compiler can count the
+// outstanding loads exactly.
+template <int kBits>
+__device__ inline void lin_load(LinStage<kBits> &st, const int8_t *__restrict__ xq, long long M,
                                 long long K, const uint8_t *__restrict__ pcodes,
-                                const uint8_t *__restrict__ pflags, long long N, int bits,
-                                long long row0, long long col0, long long k0)
+                                const uint8_t *__restrict__ pflags, long long N, long long row0,
+                                long long col0, long long k0)
 {
+    static_assert(kLinWG == 4 * kLinBN, "every thread carries 16 weights of the tile");
     const int t = threadIdx.x;
-    const long long r = row0 + (t >> 1);
-    if (r < M) {
-        const v4i *src = reinterpret_cast<const v4i *>(xq + r * K + k0 + (t & 1) * 32);
-        st.a0 = src[0];
-        st.a1 = src[1];
-    } else {
-        st.a0 = v4i{0, 0, 0, 0};
-        st.a1 = v4i{0, 0, 0, 0};
+#pragma unroll
+    for (int v = 0; v < kLinAVec; ++v) {
+        const int piece = t + v * kLinWG;              // 4 pieces of 16 bytes per row
+        long long r = row0 + (piece >> 2);
+        r = r < M ? r : M - 1;
+        st.a[v] = *reinterpret_cast<const v4i *>(xq + r * K + k0 + (piece & 3) * 16);
     }
-    const long long n = col0 + (t >> 2);
-    if (n < N) {
-        const long long e0 = n * K + k0 + (t & 3) * 16;
-        load_codes16(pcodes, e0, bits, st.codes);
-        st.flags = *reinterpret_cast<const uint16_t *>(pflags + (e0 >> 3));
-    } else {
-        st.codes[0] = st.codes[1] = st.codes[2] = st.codes[3] = 0;
-        st.flags = 0;
-    }
+    long long n = col0 + (t >> 2);
+    n = n < N ? n : N - 1;
+    const long long e0 = n * K + k0 + (t & 3) * 16;
+    load_raw16<kBits>(pcodes, e0, st.codes);
+    st.flags = *reinterpret_cast<const uint16_t *>(pflags + (e0 >> 3));
 }
 
-__device__ inline void lin_store(const LinStage &st, int bits, int8_t *__restrict__ sA,
+// Writes one step into LDS: activations as they are, weights decoded into the
+// three planes.
+template <int kBits>
+__device__ inline void lin_store(const LinStage<kBits> &st, int8_t *__restrict__ sA,
                                  int8_t *__restrict__ sB)
 {
     const int t = threadIdx.x;
-    v4i *da = reinterpret_cast<v4i *>(sA + (t >> 1) * kLinStride + (t & 1) * 32);
-    da[0] = st.a0;
-    da[1] = st.a1;
+#pragma unroll
+    for (int v = 0; v < kLinAVec; ++v) {
+        const int piece = t + v * kLinWG;
+        *reinterpret_cast<v4i *>(sA + (piece >> 2) * kLinStride +
+                                 (((piece & 3) ^ lin_swz(piece >> 2)) * 16)) = st.a[v];
+    }
+    uint32_t c[4];
+    unpack16<kBits>(st.codes, c);
     v4i w1, w2, w3;
 #pragma unroll
     for (int x = 0; x < 4; ++x) {
-        uint32_t a, b, c;
-        planes4(st.codes[x], st.flags >> (4 * x), bits, a, b, c);
+        uint32_t a, b, d;
+        planes4(c[x], st.flags >> (4 * x), kBits, a, b, d);
         w1[x] = (int)a;
         w2[x] = (int)b;
-        w3[x] = (int)c;
+        w3[x] = (int)d;
     }
-    const int off = (t >> 2) * kLinStride + (t & 3) * 16;
+    const int off = (t >> 2) * kLinStride + (((t & 3) ^ lin_swz(t >> 2)) * 16);
     *reinterpret_cast<v4i *>(sB + off) = w1;
     *reinterpret_cast<v4i *>(sB + kLinBN * kLinStride + off) = w2;
     *reinterpret_cast<v4i *>(sB + 2 * kLinBN * kLinStride + off) = w3;
+}
+
+// One reduction step of a wavefront: fragments of LDS buffer `buf`, the next
+// step decoded into the other buffer (kStore), 6 * kLinMT matrix instructions,
+// one barrier.
+template <int kBits, bool kStore>
+__device__ inline void lin_step(v16i (&acc)[kLinMT][3], const LinStage<kBits> &next,
+                                const int8_t *a_lane, const int8_t *b_lane, int swz, int half,
+                                int8_t *sA0, int8_t *sB0, int buf)
+{
+    constexpr int kABuf = kLinBM * kLinStride, kBBuf = 3 * kLinBN * kLinStride;
+    const int8_t *a_base = a_lane + buf * kABuf;
+    const int8_t *b_base = b_lane + buf * kBBuf;
+    v4i bf[kLinBK / 32][3], af[kLinBK / 32][kLinMT];
+#pragma unroll
+    for (int ks = 0; ks < kLinBK / 32; ++ks) {
+        const int chunk = ((2 * ks + half) ^ swz) * 16;
+#pragma unroll
+        for (int pl = 0; pl < 3; ++pl)
+            bf[ks][pl] = *reinterpret_cast<const v4i *>(b_base + pl * kLinBN * kLinStride + chunk);
+#pragma unroll
+        for (int mt = 0; mt < kLinMT; ++mt)
+            af[ks][mt] = *reinterpret_cast<const v4i *>(a_base + mt * 32 * kLinStride + chunk);
+    }
+    if (kStore) lin_store<kBits>(next, sA0 + (buf ^ 1) * kABuf, sB0 + (buf ^ 1) * kBBuf);
+#pragma unroll
+    for (int ks = 0; ks < kLinBK / 32; ++ks)
+#pragma unroll
+        for (int mt = 0; mt < kLinMT; ++mt)
+#pragma unroll
+            for (int pl = 0; pl < 3; ++pl)
+                acc[mt][pl] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[ks][mt], bf[ks][pl],
+                                                                    acc[mt][pl], 0, 0, 0);
+    __syncthreads();
 }
 
 // Workgroup ids are dealt round-robin to the 8 XCDs.  Each XCD takes a
 // contiguous eighth of the channel tiles and walks all row tiles of one channel
 // tile before the next, so the packed weights of its channels stay in its L2
 // while the activations stream through.
+//
+// Pipeline of a step kt: the loads of step kt+2 are issued, the fragments of
+// step kt are read from LDS buffer kt&1, step kt+1 (loaded one step ago) is
+// decoded into the other buffer, the matrix cores run, one barrier.
+template <int kBits>
 __global__ __launch_bounds__(kLinWG) void k_linear(const int8_t *__restrict__ xq, long long M,
                                                    long long K, float s_x, float z_x,
                                                    const uint8_t *__restrict__ pcodes,
                                                    const uint8_t *__restrict__ pflags,
-                                                   long long N, int bits,
+                                                   long long N,
                                                    const float *__restrict__ p,
                                                    const float *__restrict__ m,
                                                    const float *__restrict__ wconst,
@@ -226,60 +321,55 @@ __global__ __launch_bounds__(kLinWG) void k_linear(const int8_t *__restrict__ xq
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave >> 1, wn = wave & 1;        // wm in [0, kLinWM)
 
-    v16i acc[2][3];
+    v16i acc[kLinMT][3];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < kLinMT; ++a)
 #pragma unroll
         for (int b = 0; b < 3; ++b)
 #pragma unroll
             for (int c = 0; c < 16; ++c) acc[a][b][c] = 0;
 
-    LinStage st;
-    lin_load(st, xq, M, K, pcodes, pflags, N, bits, row0, col0, 0);
-    lin_store(st, bits, sA[0], sB[0]);
-    __syncthreads();
     const int steps = (int)(K / kLinBK);
-    for (int kt = 0; kt < steps; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < steps)
-            lin_load(st, xq, M, K, pcodes, pflags, N, bits, row0, col0, (long long)(kt + 1) * kLinBK);
-        const int8_t *a_base = sA[buf] + (wm * 64 + (lane & 31)) * kLinStride + 16 * (lane >> 5);
-        const int8_t *b_base = sB[buf] + (wn * 32 + (lane & 31)) * kLinStride + 16 * (lane >> 5);
-#pragma unroll
-        for (int ks = 0; ks < kLinBK / 32; ++ks) {
-            v4i bf[3];
-#pragma unroll
-            for (int pl = 0; pl < 3; ++pl)
-                bf[pl] = *reinterpret_cast<const v4i *>(b_base + pl * kLinBN * kLinStride + ks * 32);
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt) {
-                const v4i af =
-                    *reinterpret_cast<const v4i *>(a_base + mt * 32 * kLinStride + ks * 32);
-#pragma unroll
-                for (int pl = 0; pl < 3; ++pl)
-                    acc[mt][pl] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af, bf[pl], acc[mt][pl], 0, 0, 0);
-            }
-        }
-        if (kt + 1 < steps) lin_store(st, bits, sA[buf ^ 1], sB[buf ^ 1]);
-        __syncthreads();
+    LinStage<kBits> near, far;
+    lin_load<kBits>(near, xq, M, K, pcodes, pflags, N, row0, col0, 0);
+    lin_store<kBits>(near, sA[0], sB[0]);
+    if (steps > 1) lin_load<kBits>(near, xq, M, K, pcodes, pflags, N, row0, col0, kLinBK);
+    __syncthreads();
+    // row of this lane's fragments (every 32-row tile of a wavefront has the same
+    // swizzle: tiles start at multiples of 32 rows) and its chunk swizzle
+    const int8_t *a_lane = sA[0] + (wm * 32 * kLinMT + (lane & 31)) * kLinStride;
+    const int8_t *b_lane = sB[0] + (wn * 32 + (lane & 31)) * kLinStride;
+    const int swz = lin_swz(lane & 31), half = lane >> 5;
+    // the last two steps have nothing left to load / to decode: peeled, so that
+    // the steady-state body is free of branches
+    int kt = 0;
+    for (; kt + 2 < steps; ++kt) {
+        lin_load<kBits>(far, xq, M, K, pcodes, pflags, N, row0, col0, (long long)(kt + 2) * kLinBK);
+        lin_step<kBits, true>(acc, near, a_lane, b_lane, swz, half, sA[0], sB[0], kt & 1);
+        near = far;
     }
+    if (kt + 1 < steps) {
+        lin_step<kBits, true>(acc, near, a_lane, b_lane, swz, half, sA[0], sB[0], kt & 1);
+        ++kt;
+    }
+    lin_step<kBits, false>(acc, near, a_lane, b_lane, swz, half, sA[0], sB[0], kt & 1);
 
     // epilogue: C2 A1 + C4 A2 + C5 A3 + (C3 + C6), per output channel
     const long long n = col0 + wn * 32 + (lane & 31);
     if (n >= N) return;
-    const float Lf = (float)((1 << (bits - 1)) - 1);
+    const float Lf = (float)((1 << (kBits - 1)) - 1);
     const float pn = p[n], mn = m[n];
     const float s1 = pn / Lf;
     const float width = mn - pn;
     const float s2 = width / Lf;
     const float cst = z_x * wconst[n];
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
+    for (int mt = 0; mt < kLinMT; ++mt) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const long long row = row0 + wm * 64 + mt * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+            const long long row = row0 + wm * 32 * kLinMT + mt * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
             if (row < M) {
                 const int a1 = acc[mt][0][r], a2 = acc[mt][1][r], a3 = acc[mt][2][r];
                 float t = s1 * (float)a1;
