@@ -21,14 +21,8 @@ namespace pwlq {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-#ifndef LIN_MT
-#define LIN_MT 2
-#endif
-#ifndef LIN_WM
-#define LIN_WM 2
-#endif
-constexpr int kLinMT = LIN_MT;     // 32-row tiles per wavefront
-constexpr int kLinWM = LIN_WM;     // wavefronts along the rows; 2 along the channels
+constexpr int kLinMT = 3;          // 32-row tiles per wavefront (1, 2, 4 measured slower)
+constexpr int kLinWM = 2;          // wavefronts along the rows; 2 along the channels
 constexpr int kLinBM = kLinWM * 32 * kLinMT;   // activation rows per workgroup
 constexpr int kLinBN = 64;        // output channels per workgroup
 constexpr int kLinBK = 64;        // reduction elements per step
