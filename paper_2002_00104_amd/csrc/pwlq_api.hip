@@ -328,14 +328,30 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
         k_fast<<<fast_tiles, kFastWG, lds, stream>>>(tb, n_cand, bits, tcap, tile_max, gm, sse32);
         profile_mark(5, stream);
     }
+    // tiles of at most kSmallTile elements (a suffix of the tile order) get one wavefront each
+    int nt_large = 0, longest_small = 0;
+    for (const TensorRec &r : pl.recs) {
+        if (r.tile_len > kSmallTile) nt_large += r.ntiles;
+        else if (!r.fast) longest_small = std::max(longest_small, r.tile_len);
+    }
+    const int nt_small = NT - nt_large;
     if (fast_tiles < NT) {
-        const size_t stage_bytes = sizeof(float) * (size_t)((longest + kVec - 1) / kVec * kVec);
+        auto stage_bytes = [](int len) { return sizeof(float) * (size_t)((len + kVec - 1) / kVec * kVec); };
+        const int nb2 = (pl.nblk + 1) / 2;
         if (pl.nblk <= 32) {
-            k_prep<true><<<NT, kWG, sizeof(int) * ((pl.nblk + 1) / 2) * kWG + stage_bytes, stream>>>(
-                tb, n_cand, pl.nblk, tile_max, gm, offsets, sorted);
+            if (nt_large > 0 && longest > kSmallTile)
+                k_prep<true, kWG, kPerThread><<<nt_large, kWG, sizeof(int) * nb2 * kWG + stage_bytes(longest), stream>>>(
+                    tb, 0, n_cand, pl.nblk, tile_max, gm, offsets, sorted);
+            if (nt_small > 0 && longest_small > 0)
+                k_prep<true, 64, kSmallPer><<<nt_small, 64, sizeof(int) * nb2 * 64 + stage_bytes(longest_small), stream>>>(
+                    tb, nt_large, n_cand, pl.nblk, tile_max, gm, offsets, sorted);
         } else {
-            k_prep<false><<<NT, kWG, sizeof(int) * pl.nblk + stage_bytes, stream>>>(
-                tb, n_cand, pl.nblk, tile_max, gm, offsets, sorted);
+            if (nt_large > 0 && longest > kSmallTile)
+                k_prep<false, kWG, kPerThread><<<nt_large, kWG, sizeof(int) * pl.nblk + stage_bytes(longest), stream>>>(
+                    tb, 0, n_cand, pl.nblk, tile_max, gm, offsets, sorted);
+            if (nt_small > 0 && longest_small > 0)
+                k_prep<false, 64, kSmallPer><<<nt_small, 64, sizeof(int) * pl.nblk + stage_bytes(longest_small), stream>>>(
+                    tb, nt_large, n_cand, pl.nblk, tile_max, gm, offsets, sorted);
         }
         profile_mark(0, stream);
         k_search<<<(unsigned)wgs, kSearchWaves * 64, 0, stream>>>(tb, n_cand, pl.nblk, bits, ny,
@@ -347,8 +363,12 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
             tb, n_cand, sse32, gsum);
         k_flag<<<(int)pl.n_mgroups, kWG, 0, stream>>>(tb, n_cand, gm, gsum, klist);
     }
-    k_exact<<<NT, kWG, 0, stream>>>(tb, n_cand, bits, gm, sse32, klist, part64, p_star, m_out, k_star,
-                                    mse);
+    if (nt_large > 0)
+        k_exact<kWG><<<nt_large, kWG, 0, stream>>>(tb, 0, n_cand, bits, gm, sse32, klist, part64, p_star,
+                                                   m_out, k_star, mse);
+    if (nt_small > 0)
+        k_exact<64><<<nt_small, 64, 0, stream>>>(tb, nt_large, n_cand, bits, gm, sse32, klist, part64,
+                                                 p_star, m_out, k_star, mse);
     if (pl.n_mgroups > 0)
         k_final<<<(int)pl.n_mgroups, kWG, 0, stream>>>(tb, n_cand, gm, klist, part64, p_star, m_out,
                                                        k_star, mse);

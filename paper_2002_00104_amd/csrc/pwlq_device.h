@@ -20,6 +20,8 @@ constexpr int kBlk = 64;          // candidates per wavefront: lane = candidate
 constexpr int kSearchWaves = PWLQ_SEARCH_WAVES;  // wavefronts (candidate blocks) per search workgroup
 constexpr int kTileMax = 8192;    // longest run of a group handled by one workgroup
 constexpr int kPerThread = kTileMax / kWG;  // elements of a tile held by one thread
+constexpr int kSmallTile = 1024;  // tiles up to this length get one wavefront each in k_prep and k_exact
+constexpr int kSmallPer = kSmallTile / 64;
 constexpr int kUnitElems = 4096;  // small tiles are batched up to about this many elements
 constexpr int kMinUnits = 4096;   // ... unless that would leave fewer search units than this
 constexpr int kEmitChunk = 4096;  // elements per workgroup of the quantize kernel
@@ -162,25 +164,30 @@ __device__ inline int wave_or(int v)
     return __ballot(v != 0) != 0ull;
 }
 
-// Sum over the workgroup, returned to every thread.  `lds` holds kWaves doubles.
+// Sum / minimum over a workgroup of kW wavefronts, returned to every thread.
+// `lds` holds kW doubles.
+template <int kW = kWaves>
 __device__ inline double block_sum(double v, double *lds)
 {
     v = wave_sum(v);
+    if (kW == 1) return v;
     __syncthreads();
     if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = v;
     __syncthreads();
     double s = lds[0];
-    for (int i = 1; i < kWaves; ++i) s += lds[i];
+    for (int i = 1; i < kW; ++i) s += lds[i];
     return s;
 }
+template <int kW = kWaves>
 __device__ inline double block_min(double v, double *lds)
 {
     v = wave_min(v);
+    if (kW == 1) return v;
     __syncthreads();
     if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = v;
     __syncthreads();
     double s = lds[0];
-    for (int i = 1; i < kWaves; ++i) s = fmin(s, lds[i]);
+    for (int i = 1; i < kW; ++i) s = fmin(s, lds[i]);
     return s;
 }
 

@@ -29,7 +29,7 @@ constexpr int kFastWG = 512;                       // threads per workgroup
 constexpr int kFastWaves = kFastWG / 64;
 constexpr int kFastPer = kTileMax / kFastWG;       // elements of a tile held by one thread
 constexpr int kFastTMax = 2048;                    // most buckets per tile
-constexpr int kFastCrowd = 48;                     // fullest bucket the look-ups are allowed to walk
+constexpr int kFastCrowd = 64;                     // fullest bucket the look-ups may walk: this or 1/16 of the tile
 
 // Error of a tile's filter value from the binary64 prefix arithmetic: every
 // cumulative sum is within (tile length + 64) * 2^-53 of its magnitude (at most
@@ -158,8 +158,8 @@ __device__ inline void fast_candidates(const FastLds &Q, int n, int len, int Li,
     }
 }
 
-// A tile whose values crowd into a few buckets (many equal magnitudes) would
-// make every look-up walk a long bucket; it is evaluated element by element
+// A tile whose values crowd into a few buckets (many equal magnitudes: a bucket
+// holding more than 1/16 of the tile) would make every look-up walk a long bucket; it is evaluated element by element
 // instead, in binary32 with the chunked sums of the plain search kernel (all
 // lanes read the same LDS word, which is a broadcast).
 __device__ inline void fast_plain(const float *__restrict__ elems, int len, int n, int Li,
@@ -289,7 +289,8 @@ __global__ __launch_bounds__(kFastWG) void k_fast(Tables tb, int n, int bits, in
             if (i >= first && cnt[i] > fullest) fullest = cnt[i];
         }
         const int incl = wave_scan_incl(sum);
-        fullest = (__ballot(fullest > kFastCrowd) != 0ull) ? 1 : 0;
+        const int crowd = (len >> 4) > kFastCrowd ? (len >> 4) : kFastCrowd;
+        fullest = (__ballot(fullest > crowd) != 0ull) ? 1 : 0;
         if (lane == 63) { wsum[wave] = incl; wcrowd[wave] = fullest; }
         __syncthreads();
         int run = incl - sum;

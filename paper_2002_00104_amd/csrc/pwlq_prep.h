@@ -53,24 +53,28 @@ __device__ inline int bucket_of(float u)
 // Sorted layout of one tile: [pad zeros][bucket 0][bucket 1]...; the padded
 // length is a multiple of kVec and off[j] is the start of bucket j.  The tile's
 // elements stay in registers between the passes, so the weights are read from
-// memory once.  kPrivate (at most 32 buckets): every
+// memory once.  A workgroup has kT threads holding kPer elements each (256 x 32
+// for any tile, 64 x 16 for tiles of at most kSmallTile elements: one wavefront
+// per tile, so that four times as many short tiles are in flight and no barrier
+// waits on another wavefront).  kPrivate (at most 32 buckets): every
 // thread counts into its own histogram column and positions are assigned in
 // (bucket, thread, element) order, so the layout is repeatable; otherwise LDS
 // integer atomics assign positions inside a bucket in arrival order.
-template <bool kPrivate>
-__global__ __launch_bounds__(kWG) void k_prep(Tables tb, int n, int nblk,
+template <bool kPrivate, int kT, int kPer>
+__global__ __launch_bounds__(kT) void k_prep(Tables tb, int tile_begin, int n, int nblk,
                                                const float *__restrict__ tile_max,
                                                float *__restrict__ gm,
                                                int *__restrict__ offsets,
                                                float *__restrict__ sorted)
 {
-    extern __shared__ int hist[];     // kPrivate: [ceil(nblk/2)][kWG] packed pairs, else [nblk]
-    __shared__ float redm[kWaves];
-    __shared__ int redbad[kWaves];
-    __shared__ int wtot[32 * kWaves];
-    __shared__ int wpair[16 * kWaves];
-    __shared__ int scan_lds[kWaves];
-    const int t = blockIdx.x;
+    extern __shared__ int hist[];     // kPrivate: [ceil(nblk/2)][kT] packed pairs, else [nblk]
+    constexpr int kW = kT / 64;
+    __shared__ float redm[kW];
+    __shared__ int redbad[kW];
+    __shared__ int wtot[32 * kW];
+    __shared__ int wpair[16 * kW];
+    __shared__ int scan_lds[kW];
+    const int t = tile_begin + blockIdx.x;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -79,10 +83,10 @@ __global__ __launch_bounds__(kWG) void k_prep(Tables tb, int n, int nblk,
     if (r.fast) return;               // evaluated by k_fast
     const int len = ti.len;
 
-    float a[kPerThread];
+    float a[kPer];
 #pragma unroll
-    for (int e = 0; e < kPerThread; ++e) {
-        const int i = tid + e * kWG;
+    for (int e = 0; e < kPer; ++e) {
+        const int i = tid + e * kT;
         a[e] = (i < len) ? fabsf(ti.src[i]) : 0.0f;
     }
 
@@ -91,10 +95,10 @@ __global__ __launch_bounds__(kWG) void k_prep(Tables tb, int n, int nblk,
     int bad = 0;
     if (r.tpg == 1) {
 #pragma unroll
-        for (int e = 0; e < kPerThread; ++e) { bad |= (a[e] != a[e]); m = fmaxf(m, a[e]); }
+        for (int e = 0; e < kPer; ++e) { bad |= (a[e] != a[e]); m = fmaxf(m, a[e]); }
     } else {
         const int tile0 = r.tile_base + ti.group_local * r.tpg;
-        for (int j = tid; j < r.tpg; j += kWG) {
+        for (int j = tid; j < r.tpg; j += kT) {
             float v = tile_max[tile0 + j];
             bad |= (v != v);
             m = fmaxf(m, v);
@@ -103,11 +107,11 @@ __global__ __launch_bounds__(kWG) void k_prep(Tables tb, int n, int nblk,
     m = wave_max(m);
     bad = wave_or(bad);
     if (lane == 0) { redm[wave] = m; redbad[wave] = bad; }
-    if (!kPrivate) for (int i = tid; i < nblk; i += kWG) hist[i] = 0;
+    if (!kPrivate) for (int i = tid; i < nblk; i += kT) hist[i] = 0;
     __syncthreads();
     m = redm[0];
     bad = redbad[0];
-    for (int i = 1; i < kWaves; ++i) { m = fmaxf(m, redm[i]); bad |= redbad[i]; }
+    for (int i = 1; i < kW; ++i) { m = fmaxf(m, redm[i]); bad |= redbad[i]; }
     if (bad) m = __builtin_nanf("");
     if (ti.tile_in_group == 0 && tid == 0) gm[ti.group] = m;
 
@@ -123,17 +127,17 @@ __global__ __launch_bounds__(kWG) void k_prep(Tables tb, int n, int nblk,
     // each: a thread holds at most 32 elements and a wavefront 2048, so neither
     // the counts nor their prefix sums carry into the other half)
     const int nb2 = (nblk + 1) >> 1;
-    if (kPrivate) for (int w = 0; w < nb2; ++w) hist[w * kWG + tid] = 0;
+    if (kPrivate) for (int w = 0; w < nb2; ++w) hist[w * kT + tid] = 0;
 #pragma unroll
-    for (int e = 0; e < kPerThread; ++e) {
-        const int i = tid + e * kWG;
+    for (int e = 0; e < kPer; ++e) {
+        const int i = tid + e * kT;
         if (i < len) {
             const float u = usable ? to_units(a[e], m, nf) : 0.0f;
             a[e] = u;
             const int b = bucket_of(u);
             // fire-and-forget LDS add: the column is private, the atomic form only keeps
             // the updates pipelined instead of read-modify-write round trips
-            if (kPrivate) atomicAdd(&hist[(b >> 1) * kWG + tid], 1 << (16 * (b & 1)));
+            if (kPrivate) atomicAdd(&hist[(b >> 1) * kT + tid], 1 << (16 * (b & 1)));
             else atomicAdd(&hist[b], 1);
         }
     }
@@ -141,19 +145,19 @@ __global__ __launch_bounds__(kWG) void k_prep(Tables tb, int n, int nblk,
     // exclusive positions
     if (kPrivate) {
         for (int w = 0; w < nb2; ++w) {
-            const int c = hist[w * kWG + tid];
+            const int c = hist[w * kT + tid];
             const int incl = wave_scan_incl(c);             // both halves at once
-            hist[w * kWG + tid] = incl - c;                 // exclusive inside the wavefront
-            if (lane == 63) wpair[w * kWaves + wave] = incl;
+            hist[w * kT + tid] = incl - c;                 // exclusive inside the wavefront
+            if (lane == 63) wpair[w * kW + wave] = incl;
         }
         __syncthreads();
         if (wave == 0) {
-            int w[kWaves];
+            int w[kW];
             int tot = 0;
 #pragma unroll
-            for (int i = 0; i < kWaves; ++i) {
+            for (int i = 0; i < kW; ++i) {
                 w[i] = (lane < nblk)
-                           ? (wpair[(lane >> 1) * kWaves + i] >> (16 * (lane & 1))) & 0xffff
+                           ? (wpair[(lane >> 1) * kW + i] >> (16 * (lane & 1))) & 0xffff
                            : 0;
                 tot += w[i];
             }
@@ -161,13 +165,13 @@ __global__ __launch_bounds__(kWG) void k_prep(Tables tb, int n, int nblk,
             if (lane < nblk) {
                 off[lane] = pad + run;
 #pragma unroll
-                for (int i = 0; i < kWaves; ++i) { wtot[lane * kWaves + i] = run; run += w[i]; }
+                for (int i = 0; i < kW; ++i) { wtot[lane * kW + i] = run; run += w[i]; }
             }
             if (lane == 0) off[nblk] = pad + len;
         }
     } else {
         __syncthreads();
-        const int per = (nblk + kWG - 1) / kWG;
+        const int per = (nblk + kT - 1) / kT;
         const int lo = tid * per;
         int hi = lo + per;
         if (hi > nblk) hi = nblk;
@@ -184,20 +188,20 @@ __global__ __launch_bounds__(kWG) void k_prep(Tables tb, int n, int nblk,
     // pass B: scatter into the LDS image of the sorted tile, then write it out
     // with full-width coalesced stores (scattered 4-byte stores to memory cost
     // one transaction each)
-    float *stage = reinterpret_cast<float *>(hist + (kPrivate ? nb2 * kWG : nblk));
-    for (int i = tid; i < pad; i += kWG) stage[i] = 0.0f;
+    float *stage = reinterpret_cast<float *>(hist + (kPrivate ? nb2 * kT : nblk));
+    for (int i = tid; i < pad; i += kT) stage[i] = 0.0f;
     __syncthreads();
 #pragma unroll
-    for (int e = 0; e < kPerThread; ++e) {
-        const int i = tid + e * kWG;
+    for (int e = 0; e < kPer; ++e) {
+        const int i = tid + e * kT;
         if (i < len) {
             const float u = a[e];
             const int b = bucket_of(u);
             int pos;
             if (kPrivate) {
                 const int sh = 16 * (b & 1);
-                const int old = atomicAdd(&hist[(b >> 1) * kWG + tid], 1 << sh);
-                pos = wtot[b * kWaves + wave] + ((old >> sh) & 0xffff);
+                const int old = atomicAdd(&hist[(b >> 1) * kT + tid], 1 << sh);
+                pos = wtot[b * kW + wave] + ((old >> sh) & 0xffff);
             }
             else {
                 pos = atomicAdd(&hist[b], 1);
@@ -206,7 +210,7 @@ __global__ __launch_bounds__(kWG) void k_prep(Tables tb, int n, int nblk,
         }
     }
     __syncthreads();
-    for (int i = tid * 4; i < padded; i += kWG * 4)
+    for (int i = tid * 4; i < padded; i += kT * 4)
         *reinterpret_cast<float4 *>(out + i) = *reinterpret_cast<const float4 *>(stage + i);
 }
 

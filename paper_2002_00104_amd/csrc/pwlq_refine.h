@@ -112,25 +112,26 @@ struct ExactState {
 // taken one or two at a time (there are rarely more).  Single-tile groups keep
 // the lexicographic (sum, k) minimum, so the order of the list does not matter;
 // tiles of longer groups store the sums in list order.
-template <int kEpt>
+template <int kEpt, int kT>
 __device__ inline void load_tile(const float *__restrict__ src, int len,
                                  float (&a)[kEpt > 0 ? kEpt : 1])
 {
     if (kEpt > 0) {
 #pragma unroll
         for (int e = 0; e < kEpt; ++e) {
-            const int i = threadIdx.x + e * kWG;
+            const int i = threadIdx.x + e * kT;
             a[e] = (i < len) ? fabsf(src[i]) : 0.0f;
         }
     }
 }
 
-template <int kEpt>
+template <int kEpt, int kT>
 __device__ inline void exact_tile(const float *__restrict__ src, int len,
                                   const float (&a)[kEpt > 0 ? kEpt : 1], float m, int n, int bits,
                                   const int *list, int count, bool single,
                                   double *__restrict__ part, double *lds, ExactState &st)
 {
+    constexpr int kW = kT / 64;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -143,22 +144,22 @@ __device__ inline void exact_tile(const float *__restrict__ src, int len,
             if (kEpt > 0) {
 #pragma unroll
                 for (int e = 0; e < kEpt; ++e)
-                    if (tid + e * kWG < len) acc0 += exact_error_sq(q0, a[e]);
+                    if (tid + e * kT < len) acc0 += exact_error_sq(q0, a[e]);
             } else {
-                for (int i = tid; i < len; i += kWG) acc0 += exact_error_sq(q0, fabsf(src[i]));
+                for (int i = tid; i < len; i += kT) acc0 += exact_error_sq(q0, fabsf(src[i]));
             }
         } else {
             const Pieces q1 = make_pieces(m, grid_point(m, k1, n), bits);
             if (kEpt > 0) {
 #pragma unroll
                 for (int e = 0; e < kEpt; ++e) {
-                    if (tid + e * kWG < len) {
+                    if (tid + e * kT < len) {
                         acc0 += exact_error_sq(q0, a[e]);
                         acc1 += exact_error_sq(q1, a[e]);
                     }
                 }
             } else {
-                for (int i = tid; i < len; i += kWG) {
+                for (int i = tid; i < len; i += kT) {
                     const float av = fabsf(src[i]);
                     acc0 += exact_error_sq(q0, av);
                     acc1 += exact_error_sq(q1, av);
@@ -167,11 +168,15 @@ __device__ inline void exact_tile(const float *__restrict__ src, int len,
         }
         acc0 = wave_sum(acc0);
         acc1 = wave_sum(acc1);
-        __syncthreads();
-        if (lane == 0) { lds[wave * 2] = acc0; lds[wave * 2 + 1] = acc1; }
-        __syncthreads();
-        double s0 = lds[0], s1 = lds[1];
-        for (int w = 1; w < kWaves; ++w) { s0 += lds[w * 2]; s1 += lds[w * 2 + 1]; }
+        double s0 = acc0, s1 = acc1;
+        if (kW > 1) {
+            __syncthreads();
+            if (lane == 0) { lds[wave * 2] = acc0; lds[wave * 2 + 1] = acc1; }
+            __syncthreads();
+            s0 = lds[0];
+            s1 = lds[1];
+            for (int w = 1; w < kW; ++w) { s0 += lds[w * 2]; s1 += lds[w * 2 + 1]; }
+        }
         if (single) {
             if (st.best_k < 0 || s0 < st.best || (s0 == st.best && k0 < st.best_k)) {
                 st.best = s0;
@@ -188,11 +193,12 @@ __device__ inline void exact_tile(const float *__restrict__ src, int len,
     }
 }
 
-constexpr int kListCap = 2048;   // kept candidates of a single-tile group, per round
+constexpr int kListCap = 2048;   // kept candidates of a single-tile group, per round (256-thread workgroups)
+constexpr int kListCapSmall = 1024;   // ... of a one-wavefront workgroup
 
 // The thread's elements are loaded first, so that their memory latency
 // overlaps the filtering that follows.
-template <int kEpt>
+template <int kEpt, int kT, int kCap>
 __device__ inline void exact_body(const TensorRec &r, const TileInfo &ti, int t, int n, int bits,
                                   const float *__restrict__ gm, const float *__restrict__ sse32,
                                   const int *__restrict__ klist, double *__restrict__ part64,
@@ -202,7 +208,7 @@ __device__ inline void exact_body(const TensorRec &r, const TileInfo &ti, int t,
 {
     const int tid = threadIdx.x;
     float a[kEpt > 0 ? kEpt : 1];
-    load_tile<kEpt>(ti.src, ti.len, a);
+    load_tile<kEpt, kT>(ti.src, ti.len, a);
     const bool single = r.tpg == 1;
     const float m = gm[ti.group];
     const long long og = r.out_group + ti.group_local;
@@ -217,31 +223,31 @@ __device__ inline void exact_body(const TensorRec &r, const TileInfo &ti, int t,
         const int *list = klist + (long long)mg * (n + 1);
         const int count = uni(list[0]);
         double *part = part64 + (long long)(r.part_base + ti.local_tile) * n;
-        exact_tile<kEpt>(ti.src, ti.len, a, m, n, bits, list + 1, count, false, part, lds, st);
+        exact_tile<kEpt, kT>(ti.src, ti.len, a, m, n, bits, list + 1, count, false, part, lds, st);
         return;
     }
 
-    // single-tile group: filter here, a round of at most kListCap candidates at a time
+    // single-tile group: filter here, a round of at most kCap candidates at a time
     if (m == 0.0f) {
         if (tid == 0) llist[0] = 1;
         __syncthreads();
-        exact_tile<kEpt>(ti.src, ti.len, a, m, n, bits, llist, 1, true, nullptr, lds, st);
+        exact_tile<kEpt, kT>(ti.src, ti.len, a, m, n, bits, llist, 1, true, nullptr, lds, st);
     } else if (usable) {
         const float *row = sse32 + (long long)t * n;
         double mn = __builtin_inf();
-        for (int k0 = tid; k0 < n; k0 += kWG) mn = fmin(mn, (double)row[k0]);
-        mn = block_min(mn, lds);
+        for (int k0 = tid; k0 < n; k0 += kT) mn = fmin(mn, (double)row[k0]);
+        mn = block_min<kT / 64>(mn, lds);
         const double thr = keep_threshold(mn, (double)r.gcount, n, r.fast != 0);
-        for (int rbase = 0; rbase < n; rbase += kListCap) {
+        for (int rbase = 0; rbase < n; rbase += kCap) {
             __syncthreads();
             if (tid == 0) *lcount = 0;
             __syncthreads();
-            const int rend = (rbase + kListCap < n) ? rbase + kListCap : n;
-            for (int k0 = rbase + tid; k0 < rend; k0 += kWG)
+            const int rend = (rbase + kCap < n) ? rbase + kCap : n;
+            for (int k0 = rbase + tid; k0 < rend; k0 += kT)
                 if ((double)row[k0] <= thr) llist[atomicAdd(lcount, 1)] = k0 + 1;
             __syncthreads();
             const int count = uni(*lcount);
-            exact_tile<kEpt>(ti.src, ti.len, a, m, n, bits, llist, count, true, nullptr, lds, st);
+            exact_tile<kEpt, kT>(ti.src, ti.len, a, m, n, bits, llist, count, true, nullptr, lds, st);
         }
     }
     if (tid == 0) {
@@ -258,34 +264,38 @@ __device__ inline void exact_body(const TensorRec &r, const TileInfo &ti, int t,
     }
 }
 
-__global__ __launch_bounds__(kWG) void k_exact(Tables tb, int n, int bits,
-                                               const float *__restrict__ gm,
-                                               const float *__restrict__ sse32,
-                                               const int *__restrict__ klist,
-                                               double *__restrict__ part64,
-                                               float *__restrict__ p_star,
-                                               float *__restrict__ m_out,
-                                               int32_t *__restrict__ k_star,
-                                               double *__restrict__ mse)
+template <int kT>
+__global__ __launch_bounds__(kT) void k_exact(Tables tb, int tile_begin, int n, int bits,
+                                              const float *__restrict__ gm,
+                                              const float *__restrict__ sse32,
+                                              const int *__restrict__ klist,
+                                              double *__restrict__ part64,
+                                              float *__restrict__ p_star,
+                                              float *__restrict__ m_out,
+                                              int32_t *__restrict__ k_star,
+                                              double *__restrict__ mse)
 {
-    __shared__ int llist[kListCap];
+    constexpr int kCap = (kT == 64) ? kListCapSmall : kListCap;
+    __shared__ int llist[kCap];
     __shared__ int lcount;
-    __shared__ double lds[kWaves * 2];
-    const int t = blockIdx.x;
+    __shared__ double lds[(kT / 64) * 2];
+    const int t = tile_begin + blockIdx.x;
     TensorRec r;
     TileInfo ti = tile_of(tb, t, r);
-    if (ti.len <= kWG)
-        exact_body<1>(r, ti, t, n, bits, gm, sse32, klist, part64, p_star, m_out, k_star, mse, llist,
-                      &lcount, lds);
-    else if (ti.len <= 4 * kWG)
-        exact_body<4>(r, ti, t, n, bits, gm, sse32, klist, part64, p_star, m_out, k_star, mse, llist,
-                      &lcount, lds);
-    else if (ti.len <= 10 * kWG)
-        exact_body<10>(r, ti, t, n, bits, gm, sse32, klist, part64, p_star, m_out, k_star, mse, llist,
-                       &lcount, lds);
-    else
-        exact_body<0>(r, ti, t, n, bits, gm, sse32, klist, part64, p_star, m_out, k_star, mse, llist,
-                      &lcount, lds);
+#define PWLQ_EXACT(E)                                                                              \
+    exact_body<E, kT, kCap>(r, ti, t, n, bits, gm, sse32, klist, part64, p_star, m_out, k_star,    \
+                            mse, llist, &lcount, lds)
+    if (kT == 64) {                    // one wavefront per tile of at most kSmallTile elements
+        if (ti.len <= 64) PWLQ_EXACT(1);
+        else if (ti.len <= 256) PWLQ_EXACT(4);
+        else PWLQ_EXACT(kSmallPer);
+    } else {
+        if (ti.len <= kT) PWLQ_EXACT(1);
+        else if (ti.len <= 4 * kT) PWLQ_EXACT(4);
+        else if (ti.len <= 10 * kT) PWLQ_EXACT(10);
+        else PWLQ_EXACT(0);
+    }
+#undef PWLQ_EXACT
 }
 
 // ------------------------------------------------------------------- final
