@@ -112,27 +112,29 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
 
+    # timed region: exactly K steps back to back, one synchronize on each side.
+    # The library records HIP events on the launch stream around its dominant
+    # kernels (a ring of the last 64 launches) and torch events bracket the two
+    # calls of a step; all of them are read after the closing synchronize.
     pwlq.profile_enable(True)
-    e0 = torch.cuda.Event(enable_timing=True)
-    e1 = torch.cuda.Event(enable_timing=True)
-    e2 = torch.cuda.Event(enable_timing=True)
-    k_search_ms, k_emit_ms, search_ms, quant_ms = [], [], [], []
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        e0.record()
+    for i in range(args.steps):
+        ev[i][0].record()
         pwlq.search_list(tl, wl.bits, wl.n_cand, workspace=ws_search, out=out)
-        e1.record()
+        ev[i][1].record()
         pwlq.quantize_list(tl, wl.bits, out["p_star"], out["m"], workspace=ws_quant, out=qout)
-        e2.record()
-        k_search_ms.append(pwlq.profile_last_ms(0))       # waits for the kernel's end event
-        k_emit_ms.append(pwlq.profile_last_ms(1))
-        e2.synchronize()
-        search_ms.append(e0.elapsed_time(e1))
-        quant_ms.append(e1.elapsed_time(e2))
+        ev[i][2].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     pwlq.profile_enable(False)
+    recorded = min(args.steps, 64)
+    k_search_ms = [pwlq.profile_ms(0, i) for i in range(recorded)]
+    k_emit_ms = [pwlq.profile_ms(1, i) for i in range(recorded)]
+    search_ms = [e[0].elapsed_time(e[1]) for e in ev]
+    quant_ms = [e[1].elapsed_time(e[2]) for e in ev]
+    e0, e1, e2 = ev[0]
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     n_elements = sum(t.size for t in host)

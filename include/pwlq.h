@@ -255,6 +255,9 @@ void pwlq_last_search_shape(int64_t *n_tiles, int64_t *n_groups, int64_t *n_unit
  * recorded.  Process-wide, not thread-safe; off by default. */
 void pwlq_profile_enable(int on);
 double pwlq_profile_last_ms(int role);
+/* The same for an earlier launch of that role: back = 0 is the most recent one,
+ * back = 1 the one before, up to the last 64 recorded launches; -1 beyond. */
+double pwlq_profile_ms(int role, int back);
 
 /* Name of the library's kernels as they appear in a kernel trace, by role:
  * 0 search (dominant), 1 quantize, 2 prefix-sum evaluation, 3 integer inner

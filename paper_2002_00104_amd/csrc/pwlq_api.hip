@@ -237,20 +237,27 @@ int launch_status(const char *what)
 }
 
 // Optional event timing of the dominant kernels (benchmarks only).
+// A ring of the last kProfRing recorded launches per role, so that a benchmark
+// can time a run of calls without waiting inside it.
+constexpr int kProfRoles = 4, kProfRing = 64;
 bool g_profile = false;
-hipEvent_t g_ev[8];
+hipEvent_t g_ev[kProfRoles][kProfRing][2];
 bool g_ev_made = false;
-bool g_ev_valid[4] = {false, false, false, false};
+long long g_ev_count[kProfRoles] = {0, 0, 0, 0};     // launches recorded so far
 
+// idx = 2*role for the event before the kernel, 2*role+1 for the one after it
 void profile_mark(int idx, hipStream_t stream)
 {
     if (!g_profile) return;
     if (!g_ev_made) {
-        for (auto &ev : g_ev) (void)hipEventCreate(&ev);
+        for (auto &role : g_ev)
+            for (auto &slot : role)
+                for (auto &ev : slot) (void)hipEventCreate(&ev);
         g_ev_made = true;
     }
-    (void)hipEventRecord(g_ev[idx], stream);
-    if (idx & 1) g_ev_valid[idx >> 1] = true;
+    const int role = idx >> 1;
+    (void)hipEventRecord(g_ev[role][g_ev_count[role] % kProfRing][idx & 1], stream);
+    if (idx & 1) ++g_ev_count[role];
 }
 
 // Shortest tile handed to the prefix-sum evaluator by the fast search: its
@@ -312,18 +319,9 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
         const size_t lds = sizeof(double) * (size_t)(tcap + 1 + tcap / kFastP2Step + 1) +
                            sizeof(unsigned short) * (size_t)(tcap + 2) +
                            sizeof(float) * (size_t)longest_fast;
-        if (lds > 64 * 1024) {
-            static bool raised = false;          // more than 64 KiB of LDS must be asked for
-            if (!raised) {
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fast),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                   128 * 1024);
-                if (e != hipSuccess)
-                    return fail(PWLQ_EHIP, "LDS limit of the prefix-sum kernel: %s",
-                                hipGetErrorString(e));
-                raised = true;
-            }
-        }
+        static_assert(sizeof(double) * (kFastTMax + 1 + kFastTMax / kFastP2Step + 1) +
+                          sizeof(unsigned short) * (kFastTMax + 2) + sizeof(float) * kTileMax <=
+                      64 * 1024, "k_fast must fit the LDS a launch gets without asking for more");
         profile_mark(4, stream);
         k_fast<<<fast_tiles, kFastWG, lds, stream>>>(tb, n_cand, bits, tcap, tile_max, gm, sse32);
         profile_mark(5, stream);
@@ -722,14 +720,18 @@ const char *pwlq_last_error(void) { return g_error; }
 
 void pwlq_profile_enable(int on) { g_profile = on != 0; }
 
-double pwlq_profile_last_ms(int role)
+double pwlq_profile_ms(int role, int back)
 {
-    if (role < 0 || role > 3 || !g_ev_made || !g_ev_valid[role]) return -1.0;
+    if (role < 0 || role >= kProfRoles || !g_ev_made) return -1.0;
+    if (back < 0 || back >= kProfRing || back >= g_ev_count[role]) return -1.0;
+    hipEvent_t *pair = g_ev[role][(g_ev_count[role] - 1 - back) % kProfRing];
     float ms = -1.0f;
-    if (hipEventSynchronize(g_ev[2 * role + 1]) != hipSuccess) return -1.0;
-    if (hipEventElapsedTime(&ms, g_ev[2 * role], g_ev[2 * role + 1]) != hipSuccess) return -1.0;
+    if (hipEventSynchronize(pair[1]) != hipSuccess) return -1.0;
+    if (hipEventElapsedTime(&ms, pair[0], pair[1]) != hipSuccess) return -1.0;
     return (double)ms;
 }
+
+double pwlq_profile_last_ms(int role) { return pwlq_profile_ms(role, 0); }
 
 void pwlq_last_search_shape(int64_t *n_tiles, int64_t *n_groups, int64_t *n_units)
 {

@@ -287,7 +287,10 @@ __global__ __launch_bounds__(kT) void k_exact(Tables tb, int tile_begin, int n, 
                             mse, llist, &lcount, lds)
     if (kT == 64) {                    // one wavefront per tile of at most kSmallTile elements
         if (ti.len <= 64) PWLQ_EXACT(1);
+        else if (ti.len <= 128) PWLQ_EXACT(2);
         else if (ti.len <= 256) PWLQ_EXACT(4);
+        else if (ti.len <= 512) PWLQ_EXACT(8);
+        else if (ti.len <= 640) PWLQ_EXACT(10);
         else PWLQ_EXACT(kSmallPer);
     } else {
         if (ti.len <= kT) PWLQ_EXACT(1);

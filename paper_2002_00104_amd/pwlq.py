@@ -31,7 +31,7 @@ EXPORTS = (
     "pwlq_mse_workspace_bytes", "pwlq_mse_list_workspace_bytes", "pwlq_mse", "pwlq_mse_list",
     "pwlq_linear_workspace_bytes", "pwlq_linear_i8",
     "pwlq_last_error", "pwlq_last_search_shape", "pwlq_profile_enable",
-    "pwlq_profile_last_ms", "pwlq_kernel_name",
+    "pwlq_profile_last_ms", "pwlq_profile_ms", "pwlq_kernel_name",
 )
 
 
@@ -110,6 +110,8 @@ def _load() -> ctypes.CDLL:
     lib.pwlq_profile_enable.argtypes = [ci]
     lib.pwlq_profile_last_ms.restype = ctypes.c_double
     lib.pwlq_profile_last_ms.argtypes = [ci]
+    lib.pwlq_profile_ms.restype = ctypes.c_double
+    lib.pwlq_profile_ms.argtypes = [ci, ci]
     lib.pwlq_kernel_name.restype = ctypes.c_char_p
     lib.pwlq_kernel_name.argtypes = [ci]
     return lib
@@ -428,6 +430,10 @@ def profile_enable(on: bool) -> None:
 
 def profile_last_ms(role: int) -> float:
     return float(lib.pwlq_profile_last_ms(role))
+
+
+def profile_ms(role: int, back: int) -> float:
+    return float(lib.pwlq_profile_ms(role, back))
 
 
 def last_search_shape():
