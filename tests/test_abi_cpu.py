@@ -76,3 +76,65 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert lib.pwlq_quantize(fake, 4, 4, 4, 0, None, fake, fake, fake, fake, None) == 2
     assert lib.pwlq_quantize(fake, 4, 4, 9, 0, fake, fake, fake, fake, fake, None) == 1
     assert lib.pwlq_quantize(fake, 0, 4, 4, 0, fake, fake, fake, fake, fake, None) == 1
+
+
+def test_wider_entry_points_reject_bad_arguments_on_the_host(lib):
+    vp, i64, ci, sz, cf = (ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t,
+                           ctypes.c_float)
+    fake = 0x1000   # never dereferenced: every call below fails validation first
+    lib.pwlq_search_fast.restype = ci
+    lib.pwlq_search_fast.argtypes = [vp, i64, i64, ci, ci, ci, vp, vp, vp, vp, vp, sz, vp]
+    assert lib.pwlq_search_fast(None, 4, 4, 4, 10, 0, fake, fake, fake, fake, fake, 1 << 20, None) == 2
+    assert lib.pwlq_search_fast(fake, 4, 4, 4, 70000, 0, fake, fake, fake, fake, fake, 1 << 20, None) == 1
+
+    lib.pwlq_select_workspace_bytes.restype = sz
+    lib.pwlq_select_workspace_bytes.argtypes = [i64, i64, ci]
+    lib.pwlq_mse_workspace_bytes.restype = sz
+    lib.pwlq_mse_workspace_bytes.argtypes = [i64, i64, ci]
+    # one max, one sum of squares and one sum of magnitudes per tile
+    assert lib.pwlq_select_workspace_bytes(1000, 20000, 0) >= 1000 * 3 * (4 + 8 + 8)
+    assert lib.pwlq_mse_workspace_bytes(1000, 20000, 0) >= 1000 * 3 * 8
+    assert lib.pwlq_select_workspace_bytes(0, 5, 0) == 0
+    assert lib.pwlq_mse_workspace_bytes(5, 5, 3) == 0
+    lib.pwlq_select_analytic.restype = ci
+    lib.pwlq_select_analytic.argtypes = [vp, i64, i64, ci, ci, vp, vp, vp, sz, vp]
+    assert lib.pwlq_select_analytic(fake, 4, 4, 0, 3, fake, fake, fake, 1 << 20, None) == 1
+    assert lib.pwlq_select_analytic(fake, 4, 4, 0, -1, fake, fake, fake, 1 << 20, None) == 1
+    assert lib.pwlq_select_analytic(fake, 4, 4, 0, 1, None, fake, fake, 1 << 20, None) == 2
+    assert lib.pwlq_select_analytic(fake, 4, 4, 0, 1, fake, fake, None, 0, None) == 3
+    lib.pwlq_mse.restype = ci
+    lib.pwlq_mse.argtypes = [vp, i64, i64, ci, ci, vp, vp, vp, vp, sz, vp]
+    assert lib.pwlq_mse(fake, 4, 4, 1, 0, fake, fake, fake, fake, 1 << 20, None) == 1
+    assert lib.pwlq_mse(fake, 4, 4, 4, 0, fake, None, fake, fake, 1 << 20, None) == 2
+    assert lib.pwlq_mse(fake, 4, 4, 4, 0, fake, fake, fake, fake, 8, None) == 3
+
+    lib.pwlq_linear_workspace_bytes.restype = sz
+    lib.pwlq_linear_workspace_bytes.argtypes = [i64]
+    assert lib.pwlq_linear_workspace_bytes(1000) >= 4000
+    assert lib.pwlq_linear_workspace_bytes(0) == 0
+    lib.pwlq_linear_i8.restype = ci
+    lib.pwlq_linear_i8.argtypes = [vp, i64, i64, cf, cf, vp, vp, i64, ci, vp, vp, vp, vp, vp, sz, vp]
+    ok = (fake, 8, 128, 1.0, 0.0, fake, fake, 8, 4, fake, fake, fake, None, fake, 1 << 20, None)
+
+    def call(**kw):
+        names = ("xq", "M", "K", "s_x", "z_x", "codes", "flags", "N", "bits", "p", "m", "y", "acc",
+                 "ws", "ws_bytes", "stream")
+        a = dict(zip(names, ok))
+        a.update(kw)
+        return lib.pwlq_linear_i8(*[a[n] for n in names])
+
+    assert call(K=100) == 1                       # K must be a multiple of 64
+    assert call(bits=1) == 1
+    assert call(M=0) == 1
+    assert call(xq=None) == 2
+    assert call(y=None) == 2
+    assert call(codes=0x1008) == 1                # packed codes must be 16-byte aligned
+    assert call(flags=0x1001) == 1
+    assert call(ws=None) == 3
+    assert call(ws_bytes=4) == 3
+    assert call(ws=0x1010) == 3
+
+    lib.pwlq_profile_ms.restype = ctypes.c_double
+    lib.pwlq_profile_ms.argtypes = [ci, ci]
+    assert lib.pwlq_profile_ms(0, 0) == -1.0       # nothing recorded without a GPU
+    assert lib.pwlq_profile_ms(9, 0) == -1.0
