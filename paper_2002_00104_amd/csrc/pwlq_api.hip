@@ -332,19 +332,20 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
         if (r.tile_len > kSmallTile) nt_large += r.ntiles;
         else if (!r.fast) longest_small = std::max(longest_small, r.tile_len);
     }
+    if (NT - nt_large < 1024) nt_large = NT;     // too few short tiles to pay for launches of their own
     const int nt_small = NT - nt_large;
     if (fast_tiles < NT) {
         auto stage_bytes = [](int len) { return sizeof(float) * (size_t)((len + kVec - 1) / kVec * kVec); };
         const int nb2 = (pl.nblk + 1) / 2;
         if (pl.nblk <= 32) {
-            if (nt_large > 0 && longest > kSmallTile)
+            if (nt_large > 0 && (longest > kSmallTile || nt_small == 0))
                 k_prep<true, kWG, kPerThread><<<nt_large, kWG, sizeof(int) * nb2 * kWG + stage_bytes(longest), stream>>>(
                     tb, 0, n_cand, pl.nblk, tile_max, gm, offsets, sorted);
             if (nt_small > 0 && longest_small > 0)
                 k_prep<true, 64, kSmallPer><<<nt_small, 64, sizeof(int) * nb2 * 64 + stage_bytes(longest_small), stream>>>(
                     tb, nt_large, n_cand, pl.nblk, tile_max, gm, offsets, sorted);
         } else {
-            if (nt_large > 0 && longest > kSmallTile)
+            if (nt_large > 0 && (longest > kSmallTile || nt_small == 0))
                 k_prep<false, kWG, kPerThread><<<nt_large, kWG, sizeof(int) * pl.nblk + stage_bytes(longest), stream>>>(
                     tb, 0, n_cand, pl.nblk, tile_max, gm, offsets, sorted);
             if (nt_small > 0 && longest_small > 0)

@@ -296,7 +296,7 @@ __global__ __launch_bounds__(kT) void k_exact(Tables tb, int tile_begin, int n, 
         if (ti.len <= kT) PWLQ_EXACT(1);
         else if (ti.len <= 4 * kT) PWLQ_EXACT(4);
         else if (ti.len <= 10 * kT) PWLQ_EXACT(10);
-        else PWLQ_EXACT(0);
+        else PWLQ_EXACT(0);     // longer tiles are re-read per pass: holding them measured slower
     }
 #undef PWLQ_EXACT
 }
@@ -327,11 +327,17 @@ __global__ __launch_bounds__(kWG) void k_final(Tables tb, int n,
     const int count = list[0];
     const double *part = part64 + (long long)(r.part_base + gl * r.tpg) * n;
 
+    // Kept candidates are few and a group can have hundreds of tiles: one
+    // wavefront per candidate, lanes over the tiles (lane l adds tiles l, l+64, ...
+    // in order, then the 64 partial sums are added in lane order), so the order of
+    // the additions is fixed.
     double best = __builtin_inf();
     int best_slot = 0x7fffffff;
-    for (int s = tid; s < count; s += kWG) {
+    const int lane = tid & 63, wave = tid >> 6;
+    for (int s = wave; s < count; s += kWaves) {
         double v = 0.0;
-        for (int j = 0; j < r.tpg; ++j) v += part[(long long)j * n + s];
+        for (int j = lane; j < r.tpg; j += 64) v += part[(long long)j * n + s];
+        v = wave_sum(v);
         if (v < best) { best = v; best_slot = s; }
     }
     // lexicographic (sum, slot) minimum over the workgroup
