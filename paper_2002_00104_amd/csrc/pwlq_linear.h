@@ -120,11 +120,13 @@ __device__ inline void planes4(uint32_t codes, uint32_t f, int bits, uint32_t &w
     const uint32_t magmask = ((1u << (bits - 1)) - 1u) * 0x01010101u;
     const uint32_t mag = codes & magmask;
     const uint32_t sgn = (codes >> (bits - 1)) & 0x01010101u;
-    const uint32_t smask = (sgn << 8) - sgn;                            // 0xff in bytes of negative codes
+    // 0xff in the bytes that hold 1 (written so that it stays two full-rate
+    // instructions: x * 0xff would be a quarter-rate 32-bit multiply)
+    const uint32_t smask = (0x80808080u - sgn) ^ 0x80808080u;          // negative codes
     const uint32_t neg = (0x80808080u - mag) ^ 0x80808080u;            // -mag per byte (mag <= 127)
     const uint32_t val = (neg & smask) | (mag & ~smask);
     const uint32_t f01 = ((f & 0xfu) * 0x00204081u) & 0x01010101u;     // region bit of each byte
-    const uint32_t fm = (f01 << 8) - f01;                               // 0xff in tail bytes
+    const uint32_t fm = (0x80808080u - f01) ^ 0x80808080u;             // tail bytes
     w1 = val & ~fm;
     w2 = val & fm;
     w3 = (smask | 0x01010101u) & fm;
