@@ -286,9 +286,10 @@ __device__ inline void lin_step(v16i (&acc)[kLinMT][3], const LinStage<kBits> &n
 }
 
 // Workgroup ids are dealt round-robin to the 8 XCDs.  Each XCD takes a
-// contiguous eighth of the channel tiles and walks all row tiles of one channel
-// tile before the next, so the packed weights of its channels stay in its L2
-// while the activations stream through.
+// contiguous eighth of the channel tiles (their packed weights, about 1 MB,
+// stay in its L2) and walks them for one row tile before the next row tile, so
+// that the workgroups in flight on an XCD share a few activation tiles: every
+// XCD then reads the activations once instead of once per channel tile.
 //
 // Pipeline of a step kt: the loads of step kt+2 are issued, the fragments of
 // step kt are read from LDS buffer kt&1, step kt+1 (loaded one step ago) is
@@ -310,9 +311,9 @@ __global__ __launch_bounds__(kLinWG) void k_linear(const int8_t *__restrict__ xq
 
     const int xcd = blockIdx.x & 7;
     const int slot = blockIdx.x >> 3;
-    const int bn = xcd * tn_per_xcd + slot / tiles_m;
-    const int bm = slot % tiles_m;
-    if (slot / tiles_m >= tn_per_xcd || bn >= tiles_n) return;
+    const int bn = xcd * tn_per_xcd + slot % tn_per_xcd;
+    const int bm = slot / tn_per_xcd;
+    if (bm >= tiles_m || bn >= tiles_n) return;
     const long long row0 = (long long)bm * kLinBM, col0 = (long long)bn * kLinBN;
 
     const int lane = threadIdx.x & 63;
