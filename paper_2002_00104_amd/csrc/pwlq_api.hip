@@ -41,7 +41,8 @@ struct Plan {
     // workspace offsets in bytes
     size_t off_recs = 0, off_prefix = 0, off_tile_max = 0, off_gm = 0, off_offsets = 0,
            off_sorted = 0, off_sse32 = 0, off_mask = 0, off_part = 0, off_gsum = 0,
-           off_stat_max = 0, off_stat_s2 = 0, off_stat_s1 = 0, total = 0;
+           off_stat_max = 0, off_stat_s2 = 0, off_stat_s1 = 0, off_fine = 0, total = 0;
+    bool fine = false;     // tiles ordered by candidate, with per-candidate switch positions
 };
 
 // per-tile scratch beyond the tensor table
@@ -169,6 +170,8 @@ int build_plan(Plan &pl, const pwlq_tensor_desc *desc, int n_tensors, int n_cand
         pl.off_offsets = take(sizeof(int) * (size_t)tiles * (size_t)(pl.nblk + 1));
         pl.off_sorted = take(sizeof(float) * (size_t)sorted);
         pl.off_sse32 = take(sizeof(float) * (size_t)tiles * (size_t)n_cand);
+        pl.fine = n_cand <= kFineMax;
+        if (pl.fine) pl.off_fine = take(sizeof(unsigned short) * (size_t)tiles * (size_t)(n_cand + 1));
         pl.off_mask = take(sizeof(int) * (size_t)mgroups * (size_t)(n_cand + 1));
         pl.off_part = take(sizeof(double) * (size_t)parts * (size_t)n_cand);
         pl.off_gsum = take(sizeof(double) * (size_t)mgroups * (size_t)n_cand);
@@ -301,6 +304,7 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
     int *offsets = (int *)(ws + pl.off_offsets);
     float *sorted = (float *)(ws + pl.off_sorted);
     float *sse32 = (float *)(ws + pl.off_sse32);
+    unsigned short *fine = pl.fine ? (unsigned short *)(ws + pl.off_fine) : nullptr;
     int *klist = (int *)(ws + pl.off_mask);
     double *part64 = (double *)(ws + pl.off_part);
     double *gsum = (double *)(ws + pl.off_gsum);
@@ -337,24 +341,36 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
     if (fast_tiles < NT) {
         auto stage_bytes = [](int len) { return sizeof(float) * (size_t)((len + kVec - 1) / kVec * kVec); };
         const int nb2 = (pl.nblk + 1) / 2;
-        if (pl.nblk <= 32) {
-            if (nt_large > 0 && (longest > kSmallTile || nt_small == 0))
-                k_prep<true, kWG, kPerThread><<<nt_large, kWG, sizeof(int) * nb2 * kWG + stage_bytes(longest), stream>>>(
-                    tb, 0, n_cand, pl.nblk, tile_max, gm, offsets, sorted);
-            if (nt_small > 0 && longest_small > 0)
-                k_prep<true, 64, kSmallPer><<<nt_small, 64, sizeof(int) * nb2 * 64 + stage_bytes(longest_small), stream>>>(
-                    tb, nt_large, n_cand, pl.nblk, tile_max, gm, offsets, sorted);
+        const bool large = nt_large > 0 && (longest > kSmallTile || nt_small == 0);
+        const bool small = nt_small > 0 && longest_small > 0;
+        // long tiles are ordered by candidate (one bin per candidate and the switch
+        // positions written out: worth it only where buckets can be long), short
+        // ones by block of 64 candidates
+        if (pl.fine) {
+            if (large)
+                k_prep<false, true, kWG, kPerThread><<<nt_large, kWG, sizeof(int) * n_cand + stage_bytes(longest), stream>>>(
+                    tb, 0, n_cand, pl.nblk, tile_max, gm, offsets, fine, sorted);
+            if (small)
+                k_prep<true, false, 64, kSmallPer><<<nt_small, 64, sizeof(int) * nb2 * 64 + stage_bytes(longest_small), stream>>>(
+                    tb, nt_large, n_cand, pl.nblk, tile_max, gm, offsets, fine, sorted);
+        } else if (pl.nblk <= 32) {
+            if (large)
+                k_prep<true, false, kWG, kPerThread><<<nt_large, kWG, sizeof(int) * nb2 * kWG + stage_bytes(longest), stream>>>(
+                    tb, 0, n_cand, pl.nblk, tile_max, gm, offsets, fine, sorted);
+            if (small)
+                k_prep<true, false, 64, kSmallPer><<<nt_small, 64, sizeof(int) * nb2 * 64 + stage_bytes(longest_small), stream>>>(
+                    tb, nt_large, n_cand, pl.nblk, tile_max, gm, offsets, fine, sorted);
         } else {
-            if (nt_large > 0 && (longest > kSmallTile || nt_small == 0))
-                k_prep<false, kWG, kPerThread><<<nt_large, kWG, sizeof(int) * pl.nblk + stage_bytes(longest), stream>>>(
-                    tb, 0, n_cand, pl.nblk, tile_max, gm, offsets, sorted);
-            if (nt_small > 0 && longest_small > 0)
-                k_prep<false, 64, kSmallPer><<<nt_small, 64, sizeof(int) * pl.nblk + stage_bytes(longest_small), stream>>>(
-                    tb, nt_large, n_cand, pl.nblk, tile_max, gm, offsets, sorted);
+            if (large)
+                k_prep<false, false, kWG, kPerThread><<<nt_large, kWG, sizeof(int) * pl.nblk + stage_bytes(longest), stream>>>(
+                    tb, 0, n_cand, pl.nblk, tile_max, gm, offsets, fine, sorted);
+            if (small)
+                k_prep<false, false, 64, kSmallPer><<<nt_small, 64, sizeof(int) * pl.nblk + stage_bytes(longest_small), stream>>>(
+                    tb, nt_large, n_cand, pl.nblk, tile_max, gm, offsets, fine, sorted);
         }
         profile_mark(0, stream);
         k_search<<<(unsigned)wgs, kSearchWaves * 64, 0, stream>>>(tb, n_cand, pl.nblk, bits, ny,
-                                                    offsets, sorted, sse32);
+                                                    offsets, sorted, fine, pl.fine ? nt_large : 0, sse32);
         profile_mark(1, stream);
     }
     if (pl.n_mgroups > 0) {

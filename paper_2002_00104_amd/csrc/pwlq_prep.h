@@ -43,6 +43,13 @@ __device__ inline float to_units(float a, float m, float nf)
     float u = (a / m) * nf;
     return fminf(fmaxf(u, 0.0f), nf);     // also maps a NaN to 0
 }
+// smallest candidate with u <= k, 0-based
+__device__ inline int candidate_bin(float u, int n)
+{
+    int kc = (int)ceilf(u);
+    kc = kc < 1 ? 1 : kc;
+    return (kc > n ? n : kc) - 1;
+}
 __device__ inline int bucket_of(float u)
 {
     int kc = (int)ceilf(u);          // smallest candidate with u <= k
@@ -59,15 +66,21 @@ __device__ inline int bucket_of(float u)
 // waits on another wavefront).  kPrivate (at most 32 buckets): every
 // thread counts into its own histogram column and positions are assigned in
 // (bucket, thread, element) order, so the layout is repeatable; otherwise LDS
-// integer atomics assign positions inside a bucket in arrival order.
-template <bool kPrivate, int kT, int kPer>
+// integer atomics assign positions inside a bucket in arrival order.  kFine: the
+// tile is ordered by ceil(u), i.e. by the first candidate for which the element
+// is a centre element (one bin per candidate), and the position at which every
+// candidate switches from centre to tail is written as well; the search kernel
+// then knows the region of a whole vector of elements without comparing values.
+template <bool kPrivate, bool kFine, int kT, int kPer>
 __global__ __launch_bounds__(kT) void k_prep(Tables tb, int tile_begin, int n, int nblk,
                                                const float *__restrict__ tile_max,
                                                float *__restrict__ gm,
                                                int *__restrict__ offsets,
+                                               unsigned short *__restrict__ fine,
                                                float *__restrict__ sorted)
 {
-    extern __shared__ int hist[];     // kPrivate: [ceil(nblk/2)][kT] packed pairs, else [nblk]
+    static_assert(!(kPrivate && kFine), "the fine order uses shared counters");
+    extern __shared__ int hist[];     // kPrivate: [ceil(nblk/2)][kT] packed pairs, else [bins]
     constexpr int kW = kT / 64;
     __shared__ float redm[kW];
     __shared__ int redbad[kW];
@@ -107,7 +120,8 @@ __global__ __launch_bounds__(kT) void k_prep(Tables tb, int tile_begin, int n, i
     m = wave_max(m);
     bad = wave_or(bad);
     if (lane == 0) { redm[wave] = m; redbad[wave] = bad; }
-    if (!kPrivate) for (int i = tid; i < nblk; i += kT) hist[i] = 0;
+    const int bins = kFine ? n : nblk;     // kFine: one bin per candidate (ceil(u) = 1..n)
+    if (!kPrivate) for (int i = tid; i < bins; i += kT) hist[i] = 0;
     __syncthreads();
     m = redm[0];
     bad = redbad[0];
@@ -134,7 +148,7 @@ __global__ __launch_bounds__(kT) void k_prep(Tables tb, int tile_begin, int n, i
         if (i < len) {
             const float u = usable ? to_units(a[e], m, nf) : 0.0f;
             a[e] = u;
-            const int b = bucket_of(u);
+            const int b = kFine ? candidate_bin(u, n) : bucket_of(u);
             // fire-and-forget LDS add: the column is private, the atomic form only keeps
             // the updates pipelined instead of read-modify-write round trips
             if (kPrivate) atomicAdd(&hist[(b >> 1) * kT + tid], 1 << (16 * (b & 1)));
@@ -171,10 +185,10 @@ __global__ __launch_bounds__(kT) void k_prep(Tables tb, int tile_begin, int n, i
         }
     } else {
         __syncthreads();
-        const int per = (nblk + kT - 1) / kT;
+        const int per = (bins + kT - 1) / kT;
         const int lo = tid * per;
         int hi = lo + per;
-        if (hi > nblk) hi = nblk;
+        if (hi > bins) hi = bins;
         int sum = 0;
         for (int i = lo; i < hi; ++i) sum += hist[i];
         const int incl = wave_scan_incl(sum);
@@ -182,13 +196,29 @@ __global__ __launch_bounds__(kT) void k_prep(Tables tb, int tile_begin, int n, i
         __syncthreads();
         int run = incl - sum;
         for (int i = 0; i < wave; ++i) run += scan_lds[i];
-        for (int i = lo; i < hi; ++i) { int v = hist[i]; hist[i] = run; off[i] = pad + run; run += v; }
-        if (tid == 0) off[nblk] = pad + len;
+        unsigned short *fo = kFine ? fine + (long long)t * (n + 1) : nullptr;
+        for (int i = lo; i < hi; ++i) {
+            const int v = hist[i];
+            hist[i] = run;
+            if (kFine) {
+                // position of the first element whose ceil(u) exceeds i: where candidate i
+                // (1-based; entry 0 is the start) switches from centre to tail
+                fo[i] = (unsigned short)(pad + run);
+                if ((i & (kBlk - 1)) == 0) off[i >> 6] = pad + run;
+            } else {
+                off[i] = pad + run;
+            }
+            run += v;
+        }
+        if (tid == 0) {
+            off[nblk] = pad + len;
+            if (kFine) fo[n] = (unsigned short)(pad + len);
+        }
     }
     // pass B: scatter into the LDS image of the sorted tile, then write it out
     // with full-width coalesced stores (scattered 4-byte stores to memory cost
     // one transaction each)
-    float *stage = reinterpret_cast<float *>(hist + (kPrivate ? nb2 * kT : nblk));
+    float *stage = reinterpret_cast<float *>(hist + (kPrivate ? nb2 * kT : bins));
     for (int i = tid; i < pad; i += kT) stage[i] = 0.0f;
     __syncthreads();
 #pragma unroll
@@ -196,7 +226,7 @@ __global__ __launch_bounds__(kT) void k_prep(Tables tb, int tile_begin, int n, i
         const int i = tid + e * kT;
         if (i < len) {
             const float u = a[e];
-            const int b = bucket_of(u);
+            const int b = kFine ? candidate_bin(u, n) : bucket_of(u);
             int pos;
             if (kPrivate) {
                 const int sh = 16 * (b & 1);

@@ -82,10 +82,69 @@ __device__ inline float zone_mixed(const float *__restrict__ us, int begin, int 
     return outer;
 }
 
+// The same bucket when the tile is ordered by ceil(u) and `sw` is the position at
+// which this lane's candidate switches from centre to tail.  A vector of 8
+// elements that lies on one side of the lane's switch is evaluated with the
+// lane's own multiplier and offset, selected once per vector: no per-element
+// compare, no branch.  The one vector that holds the lane's switch contributes
+// nothing in that loop; every lane evaluates its own switch vector afterwards,
+// element by element (a per-lane load of 32 bytes, once per tile).
+__device__ inline void zone_mixed_fine(const float *__restrict__ us, int begin, int end, int sw,
+                                       float kf, float rc, float rt, float ct, float &sum_c,
+                                       float &sum_t)
+{
+    for (int cb = begin; cb < end; cb += kChunk) {
+        const int ce = (cb + kChunk < end) ? cb + kChunk : end;
+        float acc_c = 0.0f, acc_t = 0.0f;
+        for (int i = cb; i < ce; i += kVec) {
+            const float8 cur = load8(us + i);
+            const bool cen = sw >= i + kVec;
+            const bool tl = sw <= i;
+            const float R = cen ? rc : rt, C = cen ? 0.0f : ct;
+            float s0 = 0.0f, s1 = 0.0f;
+#pragma unroll
+            for (int e = 0; e < kVec; e += 2) {
+                const float t0 = __builtin_fmaf(cur[e], R, C);
+                const float t1 = __builtin_fmaf(cur[e + 1], R, C);
+                const float f0 = t0 - __builtin_rintf(t0);
+                const float f1 = t1 - __builtin_rintf(t1);
+                s0 = __builtin_fmaf(f0, f0, s0);
+                s1 = __builtin_fmaf(f1, f1, s1);
+            }
+            const float sv = s0 + s1;
+            acc_c += cen ? sv : 0.0f;
+            acc_t += tl ? sv : 0.0f;
+        }
+        sum_c += acc_c;
+        sum_t += acc_t;
+    }
+    // the lane's own switch vector (none if the switch falls between two vectors)
+    const bool has = (sw & (kVec - 1)) != 0;
+    const int i0 = has ? (sw & ~(kVec - 1)) : begin;
+    const float4 v0 = *reinterpret_cast<const float4 *>(us + i0);
+    const float4 v1 = *reinterpret_cast<const float4 *>(us + i0 + 4);
+    const float own[kVec] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+    float oc = 0.0f, ot = 0.0f;
+#pragma unroll
+    for (int e = 0; e < kVec; ++e) {
+        const float u = own[e];
+        const bool tail = u > kf;
+        const float t = tail ? __builtin_fmaf(u, rt, ct) : u * rc;
+        const float f = t - __builtin_rintf(t);
+        const float g = f * f;
+        oc += tail ? 0.0f : g;
+        ot += tail ? g : 0.0f;
+    }
+    sum_c += has ? oc : 0.0f;
+    sum_t += has ? ot : 0.0f;
+}
+
 __global__ __launch_bounds__(kSearchWaves * 64) void k_search(Tables tb, int n, int nblk, int bits,
                                                               int ny,
                                                               const int *__restrict__ offsets,
                                                               const float *__restrict__ sorted,
+                                                              const unsigned short *__restrict__ fine,
+                                                              int fine_tiles,
                                                               float *__restrict__ sse32)
 {
     // Workgroup ids are dealt round-robin to the 8 XCDs.  Keep the ny
@@ -129,9 +188,13 @@ __global__ __launch_bounds__(kSearchWaves * 64) void k_search(Tables tb, int n, 
         const int *off = offsets + (long long)t * (nblk + 1);
         const int lo = off[j] & ~(kVec - 1);
         const int hi = (off[j + 1] + kVec - 1) & ~(kVec - 1);
-        const float sc = zone_one_region<false>(us, 0, lo, rc, 0.0f);
-        const float sm = zone_mixed(us, lo, hi, kf, rc, rt, ct, stepc, stept);
-        const float st = zone_one_region<true>(us, hi, padded, rt, ct);
+        float sc = zone_one_region<false>(us, 0, lo, rc, 0.0f);
+        float st = zone_one_region<true>(us, hi, padded, rt, ct);
+        float sm = 0.0f;
+        // tiles before fine_tiles are ordered by candidate; that evaluation pays from
+        // about 64 elements in the bucket
+        if (t < fine_tiles && hi - lo >= kFineMin) zone_mixed_fine(us, lo, hi, fine[(long long)t * (n + 1) + k], kf, rc, rt, ct, sc, st);
+        else sm = zone_mixed(us, lo, hi, kf, rc, rt, ct, stepc, stept);
         if (live)
             sse32[(long long)t * n + (k - 1)] = (stepc * stepc) * sc + (stept * stept) * st + sm;
     }
