@@ -315,3 +315,48 @@ def test_error_statuses_write_nothing(P):
     with pytest.raises(P.PwlqError):
         P.quantize(w, 1, ps, ps)
     torch.cuda.synchronize()
+
+
+def test_weights_at_an_odd_address(P):
+    """A weight tensor that starts 4 bytes past a 16-byte boundary (a view into a
+    larger buffer): every kernel must fall back to accesses that need no alignment."""
+    import torch
+    rng = np.random.default_rng(31)
+    for C, K in ((7, 333), (3, 4099), (2, 9001)):
+        w = rng.laplace(0, 0.05, size=(C, K)).astype(np.float32)
+        buf = torch.zeros(C * K + 3, dtype=torch.float32, device="cuda")
+        for shift in (1, 3):
+            wd = buf[shift:shift + C * K].view(C, K)
+            wd.copy_(torch.from_numpy(w))
+            assert wd.data_ptr() % 16 != 0
+            r = R.search(w, 4, 200, want_curve=True)
+            for fast in (False, True):
+                g = to_np(P.search(wd, 4, 200, fast=fast))
+                assert_search_matches(g, r, f"odd address {C}x{K} shift={shift} fast={fast}")
+            p, m = torch.from_numpy(r["p_star"]).cuda(), torch.from_numpy(r["m"]).cuda()
+            q = tuple(x.cpu().numpy() for x in P.quantize(wd, 4, p, m))
+            want = R.quantize(w, 4, r["p_star"], r["m"])
+            assert_quantize_matches(q, want, "odd address quantize")
+            pc, pf, hat = P.quantize_packed(wd, 4, p, m)
+            rc, rf = R.pack(want[0], want[1], 4)
+            np.testing.assert_array_equal(pc.cpu().numpy(), rc)
+            np.testing.assert_array_equal(pf.cpu().numpy(), rf)
+            np.testing.assert_array_equal(hat.cpu().numpy().view(np.uint32), want[2].view(np.uint32))
+            np.testing.assert_allclose(P.mse(wd, 4, p, m).cpu().numpy(), R.mse(w, 4, r["p_star"], r["m"]),
+                                       rtol=1e-12)
+            ps, ms = P.select_analytic(wd, 1)
+            pr, mr = R.select_analytic(w, 1)
+            np.testing.assert_array_equal(ms.cpu().numpy(), mr)
+            np.testing.assert_allclose(ps.cpu().numpy(), pr, rtol=2e-7)
+
+
+def test_many_tensors_and_one_huge_group(P):
+    rng = np.random.default_rng(41)
+    # 200 tensors: the tensor lookup walks more than three 64-entry chunks of its table
+    shapes = [(int(rng.integers(1, 6)), int(rng.integers(1, 700))) for _ in range(200)]
+    tensors = [rng.standard_normal(s).astype(np.float32) * 0.1 for s in shapes]
+    _list_case(P, tensors, 4, 120, synth.PER_CHANNEL, "200 tensors per-channel")
+    _list_case(P, tensors, 3, 90, synth.PER_TENSOR, "200 tensors per-tensor")
+    # one group of 5 000 003 elements (611 tiles), per tensor
+    big = (0.02 * rng.standard_t(3.0, size=(1, 5_000_003))).astype(np.float32)
+    run_both(P, big, 4, 64, synth.PER_TENSOR, "one group of 5e6 elements")
