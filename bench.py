@@ -68,7 +68,8 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path "
-              "(groups are independent; see DESIGN.md for how it would shard). "
+              "(groups are independent, so it would shard by giving every GPU a "
+              "block of whole channels or tensors, with no exchange). "
               "Run with --gpus 1.", file=sys.stderr)
         return 2
 

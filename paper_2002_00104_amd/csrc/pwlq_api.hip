@@ -35,9 +35,8 @@ struct Plan {
     std::vector<TensorRec> recs;
     std::vector<int> tile_prefix, group_prefix, unit_prefix, mgroup_prefix, emit_prefix;
     int nt = 0;
-    long long n_tiles = 0, n_groups = 0, n_units = 0, n_mgroups = 0, n_part_tiles = 0, n_chunks = 0;
-    long long sorted_elems = 0;
-    int n = 0, nblk = 0, nwords = 0;
+    long long n_tiles = 0, n_groups = 0, n_units = 0, n_mgroups = 0, n_chunks = 0;
+    int n = 0, nblk = 0;
     // workspace offsets in bytes
     size_t off_recs = 0, off_prefix = 0, off_tile_max = 0, off_gm = 0, off_offsets = 0,
            off_sorted = 0, off_sse32 = 0, off_mask = 0, off_part = 0, off_gsum = 0,
@@ -67,7 +66,6 @@ int build_plan(Plan &pl, const pwlq_tensor_desc *desc, int n_tensors, int n_cand
     pl.nt = n_tensors;
     pl.n = n_cand;
     pl.nblk = (n_cand + kBlk - 1) / kBlk;
-    pl.nwords = (n_cand + 31) / 32;
 
     struct Item { int idx; int tile_len; };
     std::vector<Item> order(n_tensors);
@@ -157,8 +155,6 @@ int build_plan(Plan &pl, const pwlq_tensor_desc *desc, int n_tensors, int n_cand
     pl.n_groups = groups;
     pl.n_units = units;
     pl.n_mgroups = mgroups;
-    pl.n_part_tiles = parts;
-    pl.sorted_elems = sorted;
 
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes, 256); return at; };
