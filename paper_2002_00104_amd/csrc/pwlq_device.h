@@ -14,20 +14,11 @@ namespace pwlq {
 constexpr int kWG = 256;          // threads per workgroup (4 wavefronts of 64)
 constexpr int kWaves = kWG / 64;
 constexpr int kBlk = 64;          // candidates per wavefront: lane = candidate
-#ifndef PWLQ_SEARCH_WAVES
-#define PWLQ_SEARCH_WAVES 16
-#endif
-constexpr int kSearchWaves = PWLQ_SEARCH_WAVES;  // wavefronts (candidate blocks) per search workgroup
+constexpr int kSearchWaves = 16;  // wavefronts (candidate blocks) per search workgroup (4 and 8 measured slower)
 constexpr int kTileMax = 8192;    // longest run of a group handled by one workgroup
 constexpr int kPerThread = kTileMax / kWG;  // elements of a tile held by one thread
-#ifndef PWLQ_FINE_MAX
-#define PWLQ_FINE_MAX 2048
-#endif
-constexpr int kFineMax = PWLQ_FINE_MAX;   // most candidates for which tiles are ordered by candidate
-#ifndef PWLQ_FINE_MIN
-#define PWLQ_FINE_MIN 64
-#endif
-constexpr int kFineMin = PWLQ_FINE_MIN;   // shortest own bucket evaluated in candidate order
+constexpr int kFineMax = 2048;    // most candidates for which long tiles are ordered by candidate
+constexpr int kFineMin = 64;      // shortest own bucket evaluated in candidate order (32 and 128 measured the same)
 constexpr int kSmallTile = 1024;  // tiles up to this length get one wavefront each in k_prep and k_exact
 constexpr int kSmallPer = kSmallTile / 64;
 constexpr int kUnitElems = 4096;  // small tiles are batched up to about this many elements
