@@ -190,6 +190,24 @@ def main() -> int:
         },
     }
 
+    # What a plain device-to-device copy reaches on this chip (read + write bytes
+    # per second), as the practical ceiling beside the 8 TB/s peak.
+    ca = torch.empty(64 << 20, dtype=torch.float32, device="cuda")       # 256 MiB
+    cb = torch.empty_like(ca)
+    cb.copy_(ca)
+    torch.cuda.synchronize()
+    c0 = torch.cuda.Event(enable_timing=True)
+    c1 = torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(5):
+        cb.copy_(ca)
+    c1.record()
+    c1.synchronize()
+    copy_gbps = 5 * 2.0 * ca.numel() * 4 / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    result["quantize_roofline"]["device_copy_GBps"] = copy_gbps
+    result["quantize_roofline"]["frac_of_device_copy"] = result["quantize_roofline"]["achieved"] / copy_gbps
+    del ca, cb
+
     # Bit-packed quantizer output (b-bit code stream + 1-bit flag stream, no
     # dequantized copy): not part of the step above, timed on its own.
     layout = pwlq.PackedLayout(tl, wl.bits)
