@@ -288,7 +288,8 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
     const long long units_padded = (pl.n_units + 7) / 8 * 8;
     const long long wgs = units_padded * ny;
     if (wgs > 0x7fffffffLL) return fail(PWLQ_EINVAL, "search grid too large");
-    if (pl.n_mgroups > 65535) return fail(PWLQ_EINVAL, "too many groups longer than one tile");
+    const long long group_sum_wgs = pl.n_mgroups * (long long)((n_cand + kWG - 1) / kWG);
+    if (group_sum_wgs > 0x7fffffffLL) return fail(PWLQ_EINVAL, "too many groups longer than one tile");
 
     hipStream_t stream = (hipStream_t)stream_v;
     char *ws = (char *)workspace;
@@ -370,8 +371,7 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
         profile_mark(1, stream);
     }
     if (pl.n_mgroups > 0) {
-        k_group_sum<<<dim3((n_cand + kWG - 1) / kWG, (unsigned)pl.n_mgroups), kWG, 0, stream>>>(
-            tb, n_cand, sse32, gsum);
+        k_group_sum<<<(unsigned)group_sum_wgs, kWG, 0, stream>>>(tb, n_cand, sse32, gsum);
         k_flag<<<(int)pl.n_mgroups, kWG, 0, stream>>>(tb, n_cand, gm, gsum, klist);
     }
     if (nt_large > 0)

@@ -28,8 +28,9 @@ __global__ __launch_bounds__(kWG) void k_group_sum(Tables tb, int n,
                                                    const float *__restrict__ sse32,
                                                    double *__restrict__ gsum)
 {
-    const int mg = blockIdx.y;
-    const int k0 = blockIdx.x * kWG + threadIdx.x;
+    const int nbx = (n + kWG - 1) / kWG;             // workgroups per group
+    const int mg = blockIdx.x / nbx;
+    const int k0 = (blockIdx.x - mg * nbx) * kWG + threadIdx.x;
     const int tensor = find_tensor(tb.mgroup_prefix, tb.nt, mg);
     const TensorRec r = rec_of(tb, tensor);
     const int gl = mg - r.mgroup_base;

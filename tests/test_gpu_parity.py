@@ -360,3 +360,19 @@ def test_many_tensors_and_one_huge_group(P):
     # one group of 5 000 003 elements (611 tiles), per tensor
     big = (0.02 * rng.standard_t(3.0, size=(1, 5_000_003))).astype(np.float32)
     run_both(P, big, 4, 64, synth.PER_TENSOR, "one group of 5e6 elements")
+
+
+def test_more_than_65535_groups_of_several_tiles(P):
+    """70 000 channels of 8200 elements (two tiles each): sampled channels against the oracle."""
+    import torch
+    C, K = 70_000, 8200
+    gen = torch.Generator(device="cuda").manual_seed(3)
+    wd = torch.randn((C, K), generator=gen, device="cuda") * 0.05
+    out = to_np(P.search(wd, 4, 64))
+    fast = to_np(P.search(wd, 4, 64, fast=True))
+    rows = np.array([0, 1, 65535, 65536, 69_999])
+    w = wd[torch.from_numpy(rows).cuda()].cpu().numpy()
+    r = R.search(w, 4, 64, want_curve=True)
+    assert_search_matches({k: v[rows] for k, v in out.items()}, r, "70000 two-tile groups")
+    assert_search_matches({k: v[rows] for k, v in fast.items()}, r, "70000 two-tile groups (fast)")
+    assert (out["k_star"] > 0).all()
