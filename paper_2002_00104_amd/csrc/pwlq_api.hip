@@ -285,10 +285,13 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
     if (rc) return rc;
     // every limit is checked before the first launch: a failing call enqueues nothing
     const int ny = (pl.nblk + kSearchWaves - 1) / kSearchWaves;
-    const long long units_padded = (pl.n_units + 7) / 8 * 8;
-    const long long wgs = units_padded * ny;
+    int bpw_log2 = 0;                      // candidate blocks per unit in a workgroup, as a power of two
+    while ((1 << bpw_log2) < std::min(pl.nblk, kSearchWaves)) ++bpw_log2;
+    const int upw = kSearchWaves >> bpw_log2;       // units per workgroup
+    const long long unit_groups = (pl.n_units + upw - 1) / upw;
+    const long long wgs = (unit_groups + 7) / 8 * 8 * ny;
     if (wgs > 0x7fffffffLL) return fail(PWLQ_EINVAL, "search grid too large");
-    const long long group_sum_wgs = pl.n_mgroups * (long long)((n_cand + kWG - 1) / kWG);
+    const long long group_sum_wgs = pl.n_mgroups * (long long)((n_cand + kSumCand - 1) / kSumCand);
     if (group_sum_wgs > 0x7fffffffLL) return fail(PWLQ_EINVAL, "too many groups longer than one tile");
 
     hipStream_t stream = (hipStream_t)stream_v;
@@ -366,7 +369,7 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
                     tb, nt_large, n_cand, pl.nblk, tile_max, gm, offsets, fine, sorted);
         }
         profile_mark(0, stream);
-        k_search<<<(unsigned)wgs, kSearchWaves * 64, 0, stream>>>(tb, n_cand, pl.nblk, bits, ny,
+        k_search<<<(unsigned)wgs, kSearchWaves * 64, 0, stream>>>(tb, n_cand, pl.nblk, bits, ny, upw, bpw_log2,
                                                     offsets, sorted, fine, pl.fine ? nt_large : 0, sse32);
         profile_mark(1, stream);
     }

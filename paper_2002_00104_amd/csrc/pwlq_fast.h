@@ -205,12 +205,12 @@ __global__ __launch_bounds__(kFastWG) void k_fast(Tables tb, int n, int bits, in
     __shared__ int wcrowd[kFastWaves];
     __shared__ double wsum1[kFastWaves], wsum2[kFastWaves];
 
-    const int t = blockIdx.x;
+    int t;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
     TensorRec r;
-    TileInfo ti = tile_of(tb, t, r);
+    TileInfo ti = tile_of(tb, blockIdx.x, r, t);
     if (!r.fast) return;
     const int len = ti.len;
 

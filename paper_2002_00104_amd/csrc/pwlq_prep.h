@@ -12,9 +12,9 @@ __global__ __launch_bounds__(kWG) void k_tile_absmax(Tables tb, float *__restric
 {
     __shared__ float red[kWaves];
     __shared__ int redbad[kWaves];
-    const int t = blockIdx.x;
+    int t;
     TensorRec r;
-    TileInfo ti = tile_of(tb, t, r);
+    TileInfo ti = tile_of(tb, blockIdx.x, r, t);
     if (r.tpg == 1) return;
     float mx = 0.0f;
     int bad = 0;
@@ -87,12 +87,12 @@ __global__ __launch_bounds__(kT) void k_prep(Tables tb, int tile_begin, int n, i
     __shared__ int wtot[32 * kW];
     __shared__ int wpair[16 * kW];
     __shared__ int scan_lds[kW];
-    const int t = tile_begin + blockIdx.x;
+    int t;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
     TensorRec r;
-    TileInfo ti = tile_of(tb, t, r);
+    TileInfo ti = tile_of(tb, tile_begin + blockIdx.x, r, t);
     if (r.fast) return;               // evaluated by k_fast
     const int len = ti.len;
 

@@ -22,23 +22,34 @@ __device__ inline double keep_threshold(double mn, double count, int n, bool fas
 }
 
 // Groups spread over several tiles, step 1: add the tiles' binary32 sums in
-// binary64, in tile order.  One thread per (group, candidate); consecutive
-// threads read consecutive candidates of the same tile row.
+// binary64.  A workgroup takes 32 candidates of one group; thread (c, ph) adds
+// the tiles ph, ph+8, ph+16, ... of candidate c in that order, and the 8 partial
+// sums are added in phase order, so the result is repeatable.  (One thread per
+// candidate walking all tiles left a group of 2048 tiles to four workgroups.)
+constexpr int kSumCand = 32, kSumPhases = kWG / kSumCand;
 __global__ __launch_bounds__(kWG) void k_group_sum(Tables tb, int n,
                                                    const float *__restrict__ sse32,
                                                    double *__restrict__ gsum)
 {
-    const int nbx = (n + kWG - 1) / kWG;             // workgroups per group
+    __shared__ double part[kSumPhases][kSumCand];
+    const int nbx = (n + kSumCand - 1) / kSumCand;             // workgroups per group
     const int mg = blockIdx.x / nbx;
-    const int k0 = (blockIdx.x - mg * nbx) * kWG + threadIdx.x;
+    const int c = threadIdx.x & (kSumCand - 1), ph = threadIdx.x / kSumCand;
+    const int k0 = (blockIdx.x - mg * nbx) * kSumCand + c;
     const int tensor = find_tensor(tb.mgroup_prefix, tb.nt, mg);
     const TensorRec r = rec_of(tb, tensor);
     const int gl = mg - r.mgroup_base;
     const long long tile0 = r.tile_base + (long long)gl * r.tpg;
-    if (k0 >= n) return;
     double v = 0.0;
-    for (int j = 0; j < r.tpg; ++j) v += (double)sse32[(tile0 + j) * n + k0];
-    gsum[(long long)mg * n + k0] = v;
+    if (k0 < n)
+        for (int j = ph; j < r.tpg; j += kSumPhases) v += (double)sse32[(tile0 + j) * n + k0];
+    part[ph][c] = v;
+    __syncthreads();
+    if (ph == 0 && k0 < n) {
+        double s = part[0][c];
+        for (int i = 1; i < kSumPhases; ++i) s += part[i][c];
+        gsum[(long long)mg * n + k0] = s;
+    }
 }
 
 // Step 2: the group's minimum and the ascending list of kept candidates:
@@ -280,9 +291,9 @@ __global__ __launch_bounds__(kT) void k_exact(Tables tb, int tile_begin, int n, 
     __shared__ int llist[kCap];
     __shared__ int lcount;
     __shared__ double lds[(kT / 64) * 2];
-    const int t = tile_begin + blockIdx.x;
+    int t;
     TensorRec r;
-    TileInfo ti = tile_of(tb, t, r);
+    TileInfo ti = tile_of(tb, tile_begin + blockIdx.x, r, t);
 #define PWLQ_EXACT(E)                                                                              \
     exact_body<E, kT, kCap>(r, ti, t, n, bits, gm, sse32, klist, part64, p_star, m_out, k_star,    \
                             mse, llist, &lcount, lds)

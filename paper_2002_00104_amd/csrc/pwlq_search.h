@@ -140,31 +140,41 @@ __device__ inline void zone_mixed_fine(const float *__restrict__ us, int begin, 
 }
 
 __global__ __launch_bounds__(kSearchWaves * 64) void k_search(Tables tb, int n, int nblk, int bits,
-                                                              int ny,
+                                                              int ny, int upw, int bpw_log2,
                                                               const int *__restrict__ offsets,
                                                               const float *__restrict__ sorted,
                                                               const unsigned short *__restrict__ fine,
                                                               int fine_tiles,
                                                               float *__restrict__ sse32)
 {
-    // Workgroup ids are dealt round-robin to the 8 XCDs.  Keep the ny
-    // workgroups of one unit (same tiles, different candidate blocks) on one
-    // XCD so its L2 serves their reads, and deal units round-robin.
+    // Workgroup ids are dealt round-robin to the 8 XCDs.  The ny workgroups of
+    // one unit (same tiles, different candidate blocks) stay on one XCD so its L2
+    // serves their reads.  Unit groups are dealt to the XCDs with a rotation per
+    // row of 8, so that a pattern in the tile order (a long group cut into a full
+    // and a short tile alternates the two) does not always meet the same XCDs.
+    // With fewer than 16 candidate blocks a workgroup's wavefronts are shared by
+    // upw = 16 / bpw units (bpw: blocks rounded up to a power of two).
     const int wg = blockIdx.x;
     const int xcd = wg & 7;
     const int slot = wg >> 3;
-    const int unit = (slot / ny) * 8 + xcd;
-    const int jy = slot % ny;
+    const int q = slot / ny;
+    const int jy = slot - q * ny;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int j = jy * kSearchWaves + wave;
+    const int ug = q * 8 + ((xcd + q) & 7);
+    const int unit = ug * upw + (wave >> bpw_log2);
+    const int j = jy * kSearchWaves + (wave & ((1 << bpw_log2) - 1));
     if (unit >= tb.n_units || j >= nblk) return;
 
     const int tensor = find_tensor(tb.unit_prefix, tb.nt, unit);
     const TensorRec r = rec_of(tb, tensor);
     if (r.fast) return;               // evaluated by k_fast
-    const int first = r.tile_base + (unit - r.unit_base) * r.tpu;
+    int first = r.tile_base + (unit - r.unit_base) * r.tpu;
     int last = first + r.tpu;
     if (last > r.tile_base + r.ntiles) last = r.tile_base + r.ntiles;
+    if (r.tpg > 1) {        // one tile per unit; full tiles first (see slot_to_tile)
+        first = slot_to_tile(r, first);
+        last = first + 1;
+    }
 
     const int lane = threadIdx.x & 63;
     int k = j * kBlk + lane + 1;

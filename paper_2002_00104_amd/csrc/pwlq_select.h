@@ -41,9 +41,9 @@ __global__ __launch_bounds__(kWG) void k_stats(Tables tb, float *__restrict__ ti
     __shared__ float red[kWaves];
     __shared__ int redbad[kWaves];
     __shared__ double lds2[kWaves], lds1[kWaves];
-    const int t = blockIdx.x;
+    int t;
     TensorRec r;
-    TileInfo ti = tile_of(tb, t, r);
+    TileInfo ti = tile_of(tb, blockIdx.x, r, t);
     float mx = 0.0f;
     int bad = 0;
     double s2 = 0.0, s1 = 0.0;
@@ -179,9 +179,9 @@ __global__ __launch_bounds__(kWG) void k_mse_tile(Tables tb, int bits,
                                                   double *__restrict__ tile_sse)
 {
     __shared__ double lds[kWaves];
-    const int t = blockIdx.x;
+    int t;
     TensorRec r;
-    TileInfo ti = tile_of(tb, t, r);
+    TileInfo ti = tile_of(tb, blockIdx.x, r, t);
     const long long og = r.out_group + ti.group_local;
     const Pieces q = make_pieces(m_in[og], p_in[og], bits);
     double acc = 0.0;

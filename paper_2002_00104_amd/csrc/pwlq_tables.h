@@ -54,10 +54,25 @@ __device__ inline TensorRec rec_of(const Tables &tb, int i)
     r.fast = uni(r.fast);
     return r;
 }
-__device__ inline TileInfo tile_of(const Tables &tb, int t, TensorRec &r)
+// Tile taken by the workgroup with index `slot`, returned in t.  For tensors
+// whose groups are cut into several tiles the slots of the tensor take all full
+// tiles first and the groups' last, shorter tiles afterwards: in tile order the
+// two alternate, and because workgroups are placed on the CUs in turn every
+// other CU would get only the short ones.
+__device__ inline int slot_to_tile(const TensorRec &r, int slot)
 {
-    const int tensor = find_tensor(tb.tile_prefix, tb.nt, t);
+    if (r.tpg == 1) return slot;
+    const int ls = slot - r.tile_base;
+    const int nfull = r.ngroups * (r.tpg - 1);
+    const int g = ls < nfull ? ls / (r.tpg - 1) : ls - nfull;
+    const int tig = ls < nfull ? ls - g * (r.tpg - 1) : r.tpg - 1;
+    return r.tile_base + g * r.tpg + tig;
+}
+__device__ inline TileInfo tile_of(const Tables &tb, int slot, TensorRec &r, int &t)
+{
+    const int tensor = find_tensor(tb.tile_prefix, tb.nt, slot);
     r = rec_of(tb, tensor);
+    t = slot_to_tile(r, slot);
     return tile_info(r, tensor, t);
 }
 
