@@ -287,6 +287,8 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
     const int ny = (pl.nblk + kSearchWaves - 1) / kSearchWaves;
     int bpw_log2 = 0;                      // candidate blocks per unit in a workgroup, as a power of two
     while ((1 << bpw_log2) < std::min(pl.nblk, kSearchWaves)) ++bpw_log2;
+    // ... but a small call keeps one unit per workgroup rather than a handful of workgroups
+    while (bpw_log2 < 4 && pl.n_units / (kSearchWaves >> bpw_log2) < 2048) ++bpw_log2;
     const int upw = kSearchWaves >> bpw_log2;       // units per workgroup
     const long long unit_groups = (pl.n_units + upw - 1) / upw;
     const long long wgs = (unit_groups + 7) / 8 * 8 * ny;
