@@ -59,6 +59,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-linear", action="store_true",
                     help="skip the timing of the integer inner-product kernel")
+    ap.add_argument("--hot-path-only", action="store_true",
+                    help="time only the step (search_list + quantize_list): no packed output, "
+                         "fast search, analytic selectors or inner product")
     ap.add_argument("--only-k", type=int, default=0,
                     help="keep only the tensors whose rows have this many elements "
                          "(e.g. 9: the depthwise channels of workload 3)")
@@ -208,134 +211,140 @@ def main() -> int:
     result["quantize_roofline"]["frac_of_device_copy"] = result["quantize_roofline"]["achieved"] / copy_gbps
     del ca, cb
 
-    # Bit-packed quantizer output (b-bit code stream + 1-bit flag stream, no
-    # dequantized copy): not part of the step above, timed on its own.
-    layout = pwlq.PackedLayout(tl, wl.bits)
-    pout = (torch.empty(max(layout.code_bytes, 4), dtype=torch.uint8, device="cuda"),
-            torch.empty(max(layout.flag_bytes, 4), dtype=torch.uint8, device="cuda"), None)
-    for _ in range(2):
-        pwlq.quantize_packed_list(tl, wl.bits, out["p_star"], out["m"], layout=layout,
-                                  workspace=ws_quant, out=pout)
-    torch.cuda.synchronize()
-    reps = max(3, min(args.steps, 10))
-    e0.record()
-    for _ in range(reps):
-        pwlq.quantize_packed_list(tl, wl.bits, out["p_star"], out["m"], layout=layout,
-                                  workspace=ws_quant, out=pout)
-    e1.record()
-    e1.synchronize()
-    packed_ms = e0.elapsed_time(e1) / reps
-    packed_bytes = n_elements * (4.0 + wl.bits / 8.0 + 1.0 / 8.0)
-    result["quantize_packed"] = {
-        "ms": packed_ms,
-        "bytes_per_element": 4.0 + wl.bits / 8.0 + 1.0 / 8.0,
-        "achieved": packed_bytes / (packed_ms * 1e-3) / 1e9,
-        "peak": 8000.0,
-        "unit": "GB/s",
-        "note": "call time (table upload + kernel), w_hat not requested",
-    }
-
-    # The same search through the prefix-sum evaluator (pwlq_search_fast_list):
-    # identical outputs, far fewer operations, so its rate is quoted in
-    # evaluations *replaced* per second, not performed.
-    for _ in range(2):
-        pwlq.search_list(tl, wl.bits, wl.n_cand, workspace=ws_search, out=out, fast=True)
-    torch.cuda.synchronize()
-    pwlq.profile_enable(True)
-    fast_ms, k_fast_ms = [], []
-    for _ in range(reps):
-        e0.record()
-        pwlq.search_list(tl, wl.bits, wl.n_cand, workspace=ws_search, out=out, fast=True)
-        e1.record()
-        k_fast_ms.append(pwlq.profile_last_ms(2))
-        e1.synchronize()
-        fast_ms.append(e0.elapsed_time(e1))
-    pwlq.profile_enable(False)
-    result["search_fast"] = {
-        "ms": float(np.mean(fast_ms)),
-        "kernel": pwlq.kernel_name(2),
-        "kernel_ms": float(np.mean(k_fast_ms)),
-        "equivalent_evals_per_s": evals / (float(np.mean(fast_ms)) * 1e-3),
-        "speedup_over_exhaustive_search": float(np.mean(search_ms)) / float(np.mean(fast_ms)),
-    }
-
-    # The paper's analytic breakpoint selectors on the same weights: time of one
-    # model-level call and the error they reach relative to the exhaustive
-    # optimum of the step above (both errors evaluated by pwlq_mse_list).
-    ws_sel = torch.empty(max(256, pwlq.select_list_workspace_bytes(tl)), dtype=torch.uint8,
-                         device="cuda")
-    ws_mse = torch.empty(max(256, pwlq.mse_list_workspace_bytes(tl)), dtype=torch.uint8,
-                         device="cuda")
-    sel_out = (torch.empty(tl.n_groups, dtype=torch.float32, device="cuda"),
-               torch.empty(tl.n_groups, dtype=torch.float32, device="cuda"))
-    mse_out = torch.empty(tl.n_groups, dtype=torch.float64, device="cuda")
-    best = pwlq.mse_list(tl, wl.bits, out["p_star"], out["m"], workspace=ws_mse).clone()
-    result["analytic_selectors"] = {}
-    for name, sel in (("gauss_fit", pwlq.GAUSS_FIT), ("gauss_solve", pwlq.GAUSS_SOLVE),
-                      ("laplace_solve", pwlq.LAPLACE_SOLVE)):
+    # Beyond the step above, each timed on its own (skipped by --hot-path-only, so that a
+    # profiler summary of that run averages each kernel over the timed steps alone).
+    def extras():
+        # Bit-packed quantizer output (b-bit code stream + 1-bit flag stream, no
+        # dequantized copy): not part of the step above, timed on its own.
+        layout = pwlq.PackedLayout(tl, wl.bits)
+        pout = (torch.empty(max(layout.code_bytes, 4), dtype=torch.uint8, device="cuda"),
+                torch.empty(max(layout.flag_bytes, 4), dtype=torch.uint8, device="cuda"), None)
         for _ in range(2):
-            pwlq.select_analytic_list(tl, sel, workspace=ws_sel, out=sel_out)
+            pwlq.quantize_packed_list(tl, wl.bits, out["p_star"], out["m"], layout=layout,
+                                      workspace=ws_quant, out=pout)
         torch.cuda.synchronize()
+        reps = max(3, min(args.steps, 10))
         e0.record()
         for _ in range(reps):
-            pwlq.select_analytic_list(tl, sel, workspace=ws_sel, out=sel_out)
+            pwlq.quantize_packed_list(tl, wl.bits, out["p_star"], out["m"], layout=layout,
+                                      workspace=ws_quant, out=pout)
         e1.record()
-        for _ in range(reps):
-            pwlq.mse_list(tl, wl.bits, sel_out[0], sel_out[1], workspace=ws_mse, out=mse_out)
-        e2.record()
-        e2.synchronize()
-        ok = (best > 0) & torch.isfinite(best) & torch.isfinite(mse_out)
-        ratio = (mse_out[ok] / best[ok])
-        result["analytic_selectors"][name] = {
-            "select_ms": e0.elapsed_time(e1) / reps,
-            "mse_ms": e1.elapsed_time(e2) / reps,
-            "mse_over_grid_optimum_geomean": float(torch.exp(torch.log(ratio).mean())),
-            "mse_over_grid_optimum_max": float(ratio.max()),
-            "total_sse_over_grid_optimum": float(
-                (mse_out[ok] * tl.group_counts(ok)).sum() / (best[ok] * tl.group_counts(ok)).sum()),
+        e1.synchronize()
+        packed_ms = e0.elapsed_time(e1) / reps
+        packed_bytes = n_elements * (4.0 + wl.bits / 8.0 + 1.0 / 8.0)
+        result["quantize_packed"] = {
+            "ms": packed_ms,
+            "bytes_per_element": 4.0 + wl.bits / 8.0 + 1.0 / 8.0,
+            "achieved": packed_bytes / (packed_ms * 1e-3) / 1e9,
+            "peak": 8000.0,
+            "unit": "GB/s",
+            "note": "call time (table upload + kernel), w_hat not requested",
         }
 
-    # Consumer of the packed format (Section 4): int8 activations [4096, 4096]
-    # times a PWLQ-quantized [4096, 4096] linear weight (b = 4, Laplacian values of
-    # workload 5's kind), three integer accumulators per output on the int8 matrix
-    # cores.  `achieved` counts the multiply-adds the matrix cores execute (three
-    # planes); `algorithmic` counts one multiply-add per (row, channel, k).
-    if not args.no_linear:
-        Ml, Kl, Nl, bl = 4096, 4096, 4096, 4
-        gen = torch.Generator(device="cuda").manual_seed(7)
-        u01 = torch.rand((Nl, Kl), generator=gen, device="cuda") - 0.5
-        wlin = (-0.02 * torch.sign(u01) * torch.log1p(-2.0 * u01.abs())).contiguous()   # Laplace(0, 0.02)
-        sl = pwlq.search(wlin, bl, 100, fast=True)
-        pc, pf, _ = pwlq.quantize_packed(wlin, bl, sl["p_star"], sl["m"], want_w_hat=False)
-        xq = torch.randint(-128, 128, (Ml, Kl), generator=gen, device="cuda", dtype=torch.int8)
-        ws_lin = torch.empty(max(256, pwlq.lib.pwlq_linear_workspace_bytes(Nl)), dtype=torch.uint8,
-                             device="cuda")
-        lout = (torch.empty((Ml, Nl), dtype=torch.float32, device="cuda"), None)
+        # The same search through the prefix-sum evaluator (pwlq_search_fast_list):
+        # identical outputs, far fewer operations, so its rate is quoted in
+        # evaluations *replaced* per second, not performed.
         for _ in range(2):
-            pwlq.linear_i8(xq, 0.02, -0.5, pc, pf, Nl, bl, sl["p_star"], sl["m"], workspace=ws_lin,
-                           out=lout)
+            pwlq.search_list(tl, wl.bits, wl.n_cand, workspace=ws_search, out=out, fast=True)
         torch.cuda.synchronize()
         pwlq.profile_enable(True)
-        lin_ms = []
+        fast_ms, k_fast_ms = [], []
         for _ in range(reps):
-            pwlq.linear_i8(xq, 0.02, -0.5, pc, pf, Nl, bl, sl["p_star"], sl["m"], workspace=ws_lin,
-                           out=lout)
-            lin_ms.append(pwlq.profile_last_ms(3))
+            e0.record()
+            pwlq.search_list(tl, wl.bits, wl.n_cand, workspace=ws_search, out=out, fast=True)
+            e1.record()
+            k_fast_ms.append(pwlq.profile_last_ms(2))
+            e1.synchronize()
+            fast_ms.append(e0.elapsed_time(e1))
         pwlq.profile_enable(False)
-        lm = float(np.mean(lin_ms))
-        ops = 2.0 * Ml * Nl * Kl
-        result["linear_i8"] = {
-            "kernel": pwlq.kernel_name(3),
-            "shape": f"xq [{Ml},{Kl}] int8 x packed PWLQ weight [{Nl},{Kl}], b={bl}",
-            "kernel_ms": lm,
-            "bound": "mfma",
-            "achieved": 3.0 * ops / (lm * 1e-3) / 1e12,
-            "algorithmic": ops / (lm * 1e-3) / 1e12,
-            "peak": 5000.0,
-            "unit": "TOP/s int8 (dense MFMA)",
-            "frac": 3.0 * ops / (lm * 1e-3) / 5e15,
-            "weight_bytes_per_element": (bl + 1) / 8.0,
+        result["search_fast"] = {
+            "ms": float(np.mean(fast_ms)),
+            "kernel": pwlq.kernel_name(2),
+            "kernel_ms": float(np.mean(k_fast_ms)),
+            "equivalent_evals_per_s": evals / (float(np.mean(fast_ms)) * 1e-3),
+            "speedup_over_exhaustive_search": float(np.mean(search_ms)) / float(np.mean(fast_ms)),
         }
+
+        # The paper's analytic breakpoint selectors on the same weights: time of one
+        # model-level call and the error they reach relative to the exhaustive
+        # optimum of the step above (both errors evaluated by pwlq_mse_list).
+        ws_sel = torch.empty(max(256, pwlq.select_list_workspace_bytes(tl)), dtype=torch.uint8,
+                             device="cuda")
+        ws_mse = torch.empty(max(256, pwlq.mse_list_workspace_bytes(tl)), dtype=torch.uint8,
+                             device="cuda")
+        sel_out = (torch.empty(tl.n_groups, dtype=torch.float32, device="cuda"),
+                   torch.empty(tl.n_groups, dtype=torch.float32, device="cuda"))
+        mse_out = torch.empty(tl.n_groups, dtype=torch.float64, device="cuda")
+        best = pwlq.mse_list(tl, wl.bits, out["p_star"], out["m"], workspace=ws_mse).clone()
+        result["analytic_selectors"] = {}
+        for name, sel in (("gauss_fit", pwlq.GAUSS_FIT), ("gauss_solve", pwlq.GAUSS_SOLVE),
+                          ("laplace_solve", pwlq.LAPLACE_SOLVE)):
+            for _ in range(2):
+                pwlq.select_analytic_list(tl, sel, workspace=ws_sel, out=sel_out)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(reps):
+                pwlq.select_analytic_list(tl, sel, workspace=ws_sel, out=sel_out)
+            e1.record()
+            for _ in range(reps):
+                pwlq.mse_list(tl, wl.bits, sel_out[0], sel_out[1], workspace=ws_mse, out=mse_out)
+            e2.record()
+            e2.synchronize()
+            ok = (best > 0) & torch.isfinite(best) & torch.isfinite(mse_out)
+            ratio = (mse_out[ok] / best[ok])
+            result["analytic_selectors"][name] = {
+                "select_ms": e0.elapsed_time(e1) / reps,
+                "mse_ms": e1.elapsed_time(e2) / reps,
+                "mse_over_grid_optimum_geomean": float(torch.exp(torch.log(ratio).mean())),
+                "mse_over_grid_optimum_max": float(ratio.max()),
+                "total_sse_over_grid_optimum": float(
+                    (mse_out[ok] * tl.group_counts(ok)).sum() / (best[ok] * tl.group_counts(ok)).sum()),
+            }
+
+        # Consumer of the packed format (Section 4): int8 activations [4096, 4096]
+        # times a PWLQ-quantized [4096, 4096] linear weight (b = 4, Laplacian values of
+        # workload 5's kind), three integer accumulators per output on the int8 matrix
+        # cores.  `achieved` counts the multiply-adds the matrix cores execute (three
+        # planes); `algorithmic` counts one multiply-add per (row, channel, k).
+        if not args.no_linear:
+            Ml, Kl, Nl, bl = 4096, 4096, 4096, 4
+            gen = torch.Generator(device="cuda").manual_seed(7)
+            u01 = torch.rand((Nl, Kl), generator=gen, device="cuda") - 0.5
+            wlin = (-0.02 * torch.sign(u01) * torch.log1p(-2.0 * u01.abs())).contiguous()   # Laplace(0, 0.02)
+            sl = pwlq.search(wlin, bl, 100, fast=True)
+            pc, pf, _ = pwlq.quantize_packed(wlin, bl, sl["p_star"], sl["m"], want_w_hat=False)
+            xq = torch.randint(-128, 128, (Ml, Kl), generator=gen, device="cuda", dtype=torch.int8)
+            ws_lin = torch.empty(max(256, pwlq.lib.pwlq_linear_workspace_bytes(Nl)), dtype=torch.uint8,
+                                 device="cuda")
+            lout = (torch.empty((Ml, Nl), dtype=torch.float32, device="cuda"), None)
+            for _ in range(2):
+                pwlq.linear_i8(xq, 0.02, -0.5, pc, pf, Nl, bl, sl["p_star"], sl["m"], workspace=ws_lin,
+                               out=lout)
+            torch.cuda.synchronize()
+            pwlq.profile_enable(True)
+            lin_ms = []
+            for _ in range(reps):
+                pwlq.linear_i8(xq, 0.02, -0.5, pc, pf, Nl, bl, sl["p_star"], sl["m"], workspace=ws_lin,
+                               out=lout)
+                lin_ms.append(pwlq.profile_last_ms(3))
+            pwlq.profile_enable(False)
+            lm = float(np.mean(lin_ms))
+            ops = 2.0 * Ml * Nl * Kl
+            result["linear_i8"] = {
+                "kernel": pwlq.kernel_name(3),
+                "shape": f"xq [{Ml},{Kl}] int8 x packed PWLQ weight [{Nl},{Kl}], b={bl}",
+                "kernel_ms": lm,
+                "bound": "mfma",
+                "achieved": 3.0 * ops / (lm * 1e-3) / 1e12,
+                "algorithmic": ops / (lm * 1e-3) / 1e12,
+                "peak": 5000.0,
+                "unit": "TOP/s int8 (dense MFMA)",
+                "frac": 3.0 * ops / (lm * 1e-3) / 5e15,
+                "weight_bytes_per_element": (bl + 1) / 8.0,
+            }
+
+    if not args.hot_path_only:
+        extras()
 
     if not args.no_cpu_baseline:
         from oracle import pwlq_ref
