@@ -50,6 +50,20 @@ def _measured_traffic(workload: int, kernel: str):
         return None
 
 
+def _measured_valu(workload: int, kernel: str):
+    """VALU wavefront-instructions per launch of `kernel` from the committed
+    rocprofv3 counter run (SQ_INSTS_VALU), or None if this workload was not measured."""
+    path = os.path.join(ROOT, "paper_2002_00104_amd", "measured_traffic.json")
+    try:
+        with open(path) as f:
+            m = json.load(f)
+        if m.get("workload") != workload:
+            return None
+        return float(m["kernels"][kernel]["valu_wave_instructions"])
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -192,6 +206,14 @@ def main() -> int:
             "kernel_ms": emit_ms,
         },
     }
+
+    # Instructions the kernel really issues (it needs fewer than the plain form's 9
+    # per evaluation, hence frac > 1 above): executed lane-instructions per second
+    # against the same peak.
+    valu = None if args.only_k else _measured_valu(wl.index, pwlq.kernel_name(0))
+    if valu is not None:
+        result["roofline"]["executed_lane_ops_per_eval"] = valu * 64 / evals
+        result["roofline"]["executed_frac"] = valu * 64 / (ks * 1e-3) / PEAK_LANE_OPS
 
     # What a plain device-to-device copy reaches on this chip (read + write bytes
     # per second), as the practical ceiling beside the 8 TB/s peak.
