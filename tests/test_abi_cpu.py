@@ -138,3 +138,15 @@ def test_wider_entry_points_reject_bad_arguments_on_the_host(lib):
     lib.pwlq_profile_ms.argtypes = [ci, ci]
     assert lib.pwlq_profile_ms(0, 0) == -1.0       # nothing recorded without a GPU
     assert lib.pwlq_profile_ms(9, 0) == -1.0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asking for more exits with a message and no JSON line."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr
+    assert "{" not in r.stdout
