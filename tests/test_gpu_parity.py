@@ -376,3 +376,22 @@ def test_more_than_65535_groups_of_several_tiles(P):
     assert_search_matches({k: v[rows] for k, v in out.items()}, r, "70000 two-tile groups")
     assert_search_matches({k: v[rows] for k, v in fast.items()}, r, "70000 two-tile groups (fast)")
     assert (out["k_star"] > 0).all()
+
+
+@pytest.mark.parametrize("K,n", [(2100, 100), (1030, 100), (1030, 250), (1030, 500), (600, 700)])
+def test_workgroups_shared_by_several_units(P, K, n):
+    """Calls with many groups and fewer than 16 candidate blocks: the search kernel gives the
+    wavefronts of a workgroup to 8, 4 or 2 units.  Sampled channels against the oracle."""
+    import torch
+    C = 36_000
+    gen = torch.Generator(device="cuda").manual_seed(K + n)
+    wd = torch.randn((C, K), generator=gen, device="cuda") * 0.05
+    out = to_np(P.search(wd, 4, n))
+    fast = to_np(P.search(wd, 4, n, fast=True))
+    rows = np.array([0, 1, 7, 8, 15, 16, 17, 4095, 4096, 20_001, 35_998, 35_999])
+    w = wd[torch.from_numpy(rows).cuda()].cpu().numpy()
+    r = R.search(w, 4, n, want_curve=True)
+    assert_search_matches({k: v[rows] for k, v in out.items()}, r, f"K={K} n={n}")
+    assert_search_matches({k: v[rows] for k, v in fast.items()}, r, f"K={K} n={n} (fast)")
+    assert (out["k_star"] > 0).all()
+    np.testing.assert_array_equal(out["k_star"], fast["k_star"])
