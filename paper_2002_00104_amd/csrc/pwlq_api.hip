@@ -205,6 +205,12 @@ int upload_tables(const Plan &pl, char *ws, hipStream_t stream, Tables &tb)
         tb.one = pl.recs[0];
         return PWLQ_OK;
     }
+    // The copies below read host memory that is gone when this call returns: a
+    // graph that recorded them would read freed memory at every replay.
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &cap) == hipSuccess && cap != hipStreamCaptureStatusNone)
+        return fail(PWLQ_EINVAL, "a call with more than one tensor uploads its table and cannot be "
+                                 "recorded into a graph; record single-tensor calls");
     std::vector<int> prefix;
     prefix.reserve(5 * (size_t)(pl.nt + 1));
     prefix.insert(prefix.end(), pl.tile_prefix.begin(), pl.tile_prefix.end());
