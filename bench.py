@@ -323,37 +323,31 @@ def main() -> int:
                     (mse_out[ok] * tl.group_counts(ok)).sum() / (best[ok] * tl.group_counts(ok)).sum()),
             }
 
-        # A one-tensor workload is launch-bound: the same step (search + quantize through
-        # the single-tensor entry points, which only launch kernels) recorded once into
-        # a HIP graph and replayed.
-        if len(dev) == 1:
-            side = torch.cuda.Stream()
-            side.wait_stream(torch.cuda.current_stream())
-            with torch.cuda.stream(side):
-                for _ in range(2):
-                    o1 = pwlq.search(dev[0], wl.bits, wl.n_cand, wl.mode)
-                    pwlq.quantize(dev[0], wl.bits, o1["p_star"], o1["m"], wl.mode)
-            torch.cuda.current_stream().wait_stream(side)
-            torch.cuda.synchronize()
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph):
-                o1 = pwlq.search(dev[0], wl.bits, wl.n_cand, wl.mode)
-                pwlq.quantize(dev[0], wl.bits, o1["p_star"], o1["m"], wl.mode)
-            for _ in range(3):
-                graph.replay()
-            torch.cuda.synchronize()
-            nrep = 200
-            g0 = time.perf_counter()
-            for _ in range(nrep):
-                graph.replay()
-            torch.cuda.synchronize()
-            g1 = time.perf_counter()
-            same = bool(torch.equal(o1["k_star"], out["k_star"]))
-            result["graph_replay"] = {
-                "ms_per_step": (g1 - g0) * 1e3 / nrep,
-                "eager_ms_per_step": ms_per_step,
-                "same_k_star_as_eager": same,
-            }
+        # The same step recorded once into a HIP graph and replayed (the calls only
+        # launch kernels): what is left of the launch overhead, which is most of the
+        # time of the one-tensor workload.
+        keep = {k: v.clone() for k, v in out.items()}
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        nrep = max(20, min(200, int(200.0 / max(ms_per_step, 1e-3))))
+        g0 = time.perf_counter()
+        for _ in range(nrep):
+            graph.replay()
+        torch.cuda.synchronize()
+        g1 = time.perf_counter()
+        result["graph_replay"] = {
+            "ms_per_step": (g1 - g0) * 1e3 / nrep,
+            "eager_ms_per_step": ms_per_step,
+            "replays": nrep,
+            "same_outputs_as_eager": bool(all(torch.equal(keep[k], out[k], ) or
+                                              bool(torch.equal(torch.nan_to_num(keep[k].double()),
+                                                               torch.nan_to_num(out[k].double())))
+                                              for k in keep)),
+        }
 
         # Consumer of the packed format (Section 4): int8 activations [4096, 4096]
         # times a PWLQ-quantized [4096, 4096] linear weight (b = 4, Laplacian values of

@@ -15,11 +15,12 @@
  *     default stream) and the call returns without waiting for it.  Tensor
  *     descriptor tables are HOST arrays and are consumed before the call
  *     returns.
- *   - Stream capture: a call on one tensor (the plain entry points, or a list
- *     variant with n_tensors = 1) only launches kernels and can be recorded
- *     into a HIP graph and replayed (same pointers, new contents).  A list call
- *     with more than one tensor copies its table from host memory and returns
- *     PWLQ_EINVAL on a capturing stream.
+ *   - Stream capture: the calls only launch kernels (a list call writes its
+ *     tensor table into the workspace through kernel arguments) and can be
+ *     recorded into a HIP graph and replayed (same pointers, new contents).
+ *     Exception: a list call whose table exceeds 56 KB (about 400 tensors)
+ *     copies it from host memory instead and returns PWLQ_EINVAL on a
+ *     capturing stream.
  *   - Return value: a pwlq_status.  On any status other than PWLQ_OK nothing
  *     was enqueued and no output is written; pwlq_last_error() describes it.
  *   - Valid ranges: 2 <= bits <= 8, 1 <= n_cand <= 65535, C >= 1, K >= 1,

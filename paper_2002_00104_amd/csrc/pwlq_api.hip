@@ -193,9 +193,13 @@ int check_workspace(const Plan &pl, const void *workspace, size_t bytes)
     return PWLQ_OK;
 }
 
-// Copies the tensor table into the head of the workspace and returns the
-// device-side view.  The host vectors are pageable, so the runtime stages
-// them before hipMemcpyAsync returns.
+// Writes the tensor table into the head of the workspace and returns the
+// device-side view.  Tables of up to kUploadMaxBytes travel in the arguments of
+// k_upload launches (asynchronous, nothing on the host has to outlive the call,
+// recordable into a graph); longer ones are copied from host memory, which the
+// runtime stages before hipMemcpyAsync returns, and cannot be recorded.
+constexpr size_t kUploadMaxBytes = 16 * sizeof(UploadChunk);
+
 int upload_tables(const Plan &pl, char *ws, hipStream_t stream, Tables &tb)
 {
     memset(&tb, 0, sizeof(tb));
@@ -205,25 +209,36 @@ int upload_tables(const Plan &pl, char *ws, hipStream_t stream, Tables &tb)
         tb.one = pl.recs[0];
         return PWLQ_OK;
     }
-    // The copies below read host memory that is gone when this call returns: a
-    // graph that recorded them would read freed memory at every replay.
-    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
-    if (hipStreamIsCapturing(stream, &cap) == hipSuccess && cap != hipStreamCaptureStatusNone)
-        return fail(PWLQ_EINVAL, "a call with more than one tensor uploads its table and cannot be "
-                                 "recorded into a graph; record single-tensor calls");
-    std::vector<int> prefix;
-    prefix.reserve(5 * (size_t)(pl.nt + 1));
-    prefix.insert(prefix.end(), pl.tile_prefix.begin(), pl.tile_prefix.end());
-    prefix.insert(prefix.end(), pl.group_prefix.begin(), pl.group_prefix.end());
-    prefix.insert(prefix.end(), pl.unit_prefix.begin(), pl.unit_prefix.end());
-    prefix.insert(prefix.end(), pl.mgroup_prefix.begin(), pl.mgroup_prefix.end());
-    prefix.insert(prefix.end(), pl.emit_prefix.begin(), pl.emit_prefix.end());
-    hipError_t e = hipMemcpyAsync(ws + pl.off_recs, pl.recs.data(),
-                                  sizeof(TensorRec) * (size_t)pl.nt, hipMemcpyHostToDevice, stream);
-    if (e == hipSuccess)
-        e = hipMemcpyAsync(ws + pl.off_prefix, prefix.data(), sizeof(int) * prefix.size(),
-                           hipMemcpyHostToDevice, stream);
-    if (e != hipSuccess) return fail(PWLQ_EHIP, "table upload: %s", hipGetErrorString(e));
+    // host image of [off_recs, off_prefix + prefix bytes): records, padding, the five prefix arrays
+    static_assert(sizeof(TensorRec) % 4 == 0, "the table is copied in 32-bit words");
+    const size_t prefix_bytes = sizeof(int) * 5 * (size_t)(pl.nt + 1);
+    const size_t bytes = pl.off_prefix - pl.off_recs + prefix_bytes;
+    std::vector<unsigned int> image(bytes / 4, 0u);
+    memcpy(image.data(), pl.recs.data(), sizeof(TensorRec) * (size_t)pl.nt);
+    int *prefix = reinterpret_cast<int *>(image.data() + (pl.off_prefix - pl.off_recs) / 4);
+    const std::vector<int> *parts[5] = {&pl.tile_prefix, &pl.group_prefix, &pl.unit_prefix,
+                                        &pl.mgroup_prefix, &pl.emit_prefix};
+    for (int i = 0; i < 5; ++i)
+        memcpy(prefix + (size_t)i * (pl.nt + 1), parts[i]->data(), sizeof(int) * (size_t)(pl.nt + 1));
+    if (bytes <= kUploadMaxBytes) {
+        UploadChunk chunk;
+        for (size_t w0 = 0; w0 < image.size(); w0 += kUploadWords) {
+            const size_t nw = std::min((size_t)kUploadWords, image.size() - w0);
+            memcpy(chunk.words, image.data() + w0, nw * 4);
+            k_upload<<<1, kWG, 0, stream>>>(chunk, reinterpret_cast<unsigned int *>(ws + pl.off_recs) + w0,
+                                            (int)nw);
+        }
+        if (hipGetLastError() != hipSuccess) return fail(PWLQ_EHIP, "table upload launch failed");
+    } else {
+        // this copy reads host memory that is gone when the call returns: a graph that
+        // recorded it would read freed memory at every replay
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(stream, &cap) == hipSuccess && cap != hipStreamCaptureStatusNone)
+            return fail(PWLQ_EINVAL, "a call with this many tensors copies its table from host memory "
+                                     "and cannot be recorded into a graph");
+        hipError_t e = hipMemcpyAsync(ws + pl.off_recs, image.data(), bytes, hipMemcpyHostToDevice, stream);
+        if (e != hipSuccess) return fail(PWLQ_EHIP, "table upload: %s", hipGetErrorString(e));
+    }
     tb.recs = reinterpret_cast<const TensorRec *>(ws + pl.off_recs);
     const int *p = reinterpret_cast<const int *>(ws + pl.off_prefix);
     tb.tile_prefix = p;

@@ -76,4 +76,17 @@ __device__ inline TileInfo tile_of(const Tables &tb, int slot, TensorRec &r, int
     return tile_info(r, tensor, t);
 }
 
+// The per-call tables reach the device inside kernel arguments: no host memory
+// has to outlive the call, the copy is ordered on the stream like any launch and
+// it can be recorded into a graph.  One launch carries kUploadWords 32-bit words.
+constexpr int kUploadWords = 896;           // 3584 bytes of the 4 KB a launch may pass
+struct UploadChunk {
+    unsigned int words[kUploadWords];
+};
+__global__ __launch_bounds__(kWG) void k_upload(UploadChunk c, unsigned int *__restrict__ dst,
+                                                int nwords)
+{
+    for (int i = threadIdx.x; i < nwords; i += kWG) dst[i] = c.words[i];
+}
+
 } // namespace pwlq

@@ -65,33 +65,49 @@ def test_search_and_quantize_replay_from_a_graph(shape, mode, bits, n, fast):
                                     R.quantize(w, bits, ps, ms, mode), "graph replay")
 
 
-def test_list_call_with_several_tensors_refuses_capture():
-    """The table upload of a list call reads host memory that is gone after the call:
-    on a capturing stream the call returns an error and records nothing."""
+def test_list_calls_replay_from_a_graph():
+    """A list call writes its table through kernel arguments, so it can be recorded too."""
     import torch
     from paper_2002_00104_amd import pwlq as P
 
     rng = np.random.default_rng(6)
-    tensors = [torch.from_numpy(rng.standard_normal((8, 100)).astype(np.float32)).cuda()
-               for _ in range(3)]
+    shapes = [(8, 100), (3, 9000), (20, 33)]
+    tensors = [torch.from_numpy(rng.standard_normal(s).astype(np.float32)).cuda() for s in shapes]
     tl = P.TensorList(tensors, synth.PER_CHANNEL)
     ws = torch.empty(P.search_list_workspace_bytes(tl, 4, 50), dtype=torch.uint8, device="cuda")
+    wq = torch.empty(max(256, P.quantize_list_workspace_bytes(tl, 4)), dtype=torch.uint8, device="cuda")
     out = P.alloc_search_outputs(tl.n_groups, "cuda")
-    eager = {k: v.clone() for k, v in P.search_list(tl, 4, 50, workspace=ws, out=out).items()}
+    qout = P.alloc_quantize_outputs(tl.n_elements, "cuda")
+    P.search_list(tl, 4, 50, workspace=ws, out=out)
+    P.quantize_list(tl, 4, out["p_star"], out["m"], workspace=wq, out=qout)
     torch.cuda.synchronize()
     g = torch.cuda.CUDAGraph()
-    raised = False
     with torch.cuda.graph(g):
-        out["mse"].zero_()                       # the recorded graph is not empty
-        try:
-            P.search_list(tl, 4, 50, workspace=ws, out=out)
-        except P.PwlqError as e:
-            raised = True
-            assert "graph" in str(e)
-    assert raised
+        P.search_list(tl, 4, 50, workspace=ws, out=out)
+        P.quantize_list(tl, 4, out["p_star"], out["m"], workspace=wq, out=qout)
     torch.cuda.synchronize()
-    # the library still works afterwards
-    again = P.search_list(tl, 4, 50, workspace=ws, out=out)
-    torch.cuda.synchronize()
-    for k in eager:
-        assert torch.equal(eager[k], again[k])
+    for rep in range(3):
+        for t, s in zip(tensors, shapes):        # eager work between the replays
+            t.copy_(torch.from_numpy((rng.standard_normal(s) * 0.07).astype(np.float32)))
+        ws.zero_()                               # the table in the workspace head is rewritten by the graph
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = {k: v.clone() for k, v in out.items()}
+        gq = tuple(t.clone() for t in qout)
+        eager = P.search_list(tl, 4, 50, workspace=ws, out=P.alloc_search_outputs(tl.n_groups, "cuda"))
+        eq = P.quantize_list(tl, 4, eager["p_star"], eager["m"], workspace=wq,
+                             out=P.alloc_quantize_outputs(tl.n_elements, "cuda"))
+        torch.cuda.synchronize()
+        for k in ("k_star", "p_star", "m", "mse"):
+            assert torch.equal(got[k], eager[k]), f"replay {rep}: {k}"
+        for a, b in zip(gq, eq):
+            assert torch.equal(a, b), f"replay {rep}: quantizer output"
+    w = np.concatenate([t.cpu().numpy().reshape(-1) for t in tensors])
+    go = 0
+    for t in tensors:
+        r = R.search(t.cpu().numpy(), 4, 50, synth.PER_CHANNEL, want_curve=True)
+        C = t.shape[0]
+        assert_search_matches({k: v[go:go + C].cpu().numpy() for k, v in got.items()}, r, "list graph replay")
+        go += C
+    del w

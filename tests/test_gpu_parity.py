@@ -357,6 +357,10 @@ def test_many_tensors_and_one_huge_group(P):
     tensors = [rng.standard_normal(s).astype(np.float32) * 0.1 for s in shapes]
     _list_case(P, tensors, 4, 120, synth.PER_CHANNEL, "200 tensors per-channel")
     _list_case(P, tensors, 3, 90, synth.PER_TENSOR, "200 tensors per-tensor")
+    # 600 tensors: the table is too long for kernel arguments and is copied from host memory
+    shapes = [(int(rng.integers(1, 4)), int(rng.integers(1, 200))) for _ in range(600)]
+    tensors = [rng.standard_normal(s).astype(np.float32) * 0.1 for s in shapes]
+    _list_case(P, tensors, 4, 70, synth.PER_CHANNEL, "600 tensors per-channel")
     # one group of 5 000 003 elements (611 tiles), per tensor
     big = (0.02 * rng.standard_t(3.0, size=(1, 5_000_003))).astype(np.float32)
     run_both(P, big, 4, 64, synth.PER_TENSOR, "one group of 5e6 elements")
