@@ -150,3 +150,24 @@ def test_bench_refuses_more_than_one_gpu():
     assert r.returncode != 0
     assert "one GPU" in r.stderr
     assert "{" not in r.stdout
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/pwlq.h compiles as C99 on its own (no HIP or C++ needed by a caller)."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("gcc not found")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    names = sorted(set(re.findall(r"\b(pwlq_[a-z0-9_]+)\s*\(", open(os.path.join(root, "include", "pwlq.h")).read())))
+    assert len(names) > 20
+    src = tmp_path / "use_header.c"
+    body = "\n".join(f"    table[{i}] = (void (*)(void))&{n};" for i, n in enumerate(names))
+    src.write_text('#include "pwlq.h"\n'
+                   f"void (*table[{len(names)}])(void);\n"
+                   "void fill(void)\n{\n" + body + "\n}\n")
+    r = subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-c",
+                        "-I", os.path.join(root, "include"), str(src), "-o", str(tmp_path / "use_header.o")],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stderr
