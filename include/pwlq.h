@@ -18,7 +18,7 @@
  *   - Stream capture: the calls only launch kernels (a list call writes its
  *     tensor table into the workspace through kernel arguments) and can be
  *     recorded into a HIP graph and replayed (same pointers, new contents).
- *     Exception: a list call whose table exceeds 56 KB (about 400 tensors)
+ *     Exception: a list call whose table exceeds 63 KB (about 500 tensors)
  *     copies it from host memory instead and returns PWLQ_EINVAL on a
  *     capturing stream.
  *   - Return value: a pwlq_status.  On any status other than PWLQ_OK nothing

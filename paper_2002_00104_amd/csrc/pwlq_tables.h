@@ -79,7 +79,7 @@ __device__ inline TileInfo tile_of(const Tables &tb, int slot, TensorRec &r, int
 // The per-call tables reach the device inside kernel arguments: no host memory
 // has to outlive the call, the copy is ordered on the stream like any launch and
 // it can be recorded into a graph.  One launch carries kUploadWords 32-bit words.
-constexpr int kUploadWords = 896;           // 3584 bytes of the 4 KB a launch may pass
+constexpr int kUploadWords = 1016;          // 4064 bytes of the 4 KB a launch may pass
 struct UploadChunk {
     unsigned int words[kUploadWords];
 };
