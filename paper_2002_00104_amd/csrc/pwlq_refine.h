@@ -246,17 +246,20 @@ __device__ inline void exact_body(const TensorRec &r, const TileInfo &ti, int t,
         exact_tile<kEpt, kT>(ti.src, ti.len, a, m, n, bits, llist, 1, true, nullptr, lds, st);
     } else if (usable) {
         const float *row = sse32 + (long long)t * n;
-        double mn = __builtin_inf();
-        for (int k0 = tid; k0 < n; k0 += kT) mn = fmin(mn, (double)row[k0]);
-        mn = block_min<kT / 64>(mn, lds);
+        float mnf = __builtin_inff();
+        for (int k0 = tid; k0 < n; k0 += kT) mnf = fminf(mnf, row[k0]);
+        const double mn = block_min<kT / 64>((double)mnf, lds);
         const double thr = keep_threshold(mn, (double)r.gcount, n, r.fast != 0);
+        // the sums are binary32: v <= thr exactly when v <= the largest binary32 value not above thr
+        float thrf = (float)thr;
+        if ((double)thrf > thr) thrf = __int_as_float(__float_as_int(thrf) - 1);   // thr >= 0: the value below
         for (int rbase = 0; rbase < n; rbase += kCap) {
             __syncthreads();
             if (tid == 0) *lcount = 0;
             __syncthreads();
             const int rend = (rbase + kCap < n) ? rbase + kCap : n;
             for (int k0 = rbase + tid; k0 < rend; k0 += kT)
-                if ((double)row[k0] <= thr) llist[atomicAdd(lcount, 1)] = k0 + 1;
+                if (row[k0] <= thrf) llist[atomicAdd(lcount, 1)] = k0 + 1;
             __syncthreads();
             const int count = uni(*lcount);
             exact_tile<kEpt, kT>(ti.src, ti.len, a, m, n, bits, llist, count, true, nullptr, lds, st);
