@@ -123,6 +123,7 @@ __global__ __launch_bounds__(kWG) void k_emit(Tables tb, int bits,
 // workgroup assembles its 256*bits code bytes and 256 flag bytes in LDS and
 // writes them out as whole words; w_hat is optional.
 constexpr int kPackPass = 8 * kWG;      // elements per pass of a workgroup
+static_assert(kEmitChunk % kPackPass == 0 && kEmitChunk % (4 * kWG) == 0, "a chunk is a whole number of passes");
 
 __global__ __launch_bounds__(kWG) void k_emit_packed(Tables tb, int bits,
                                                      const float *__restrict__ p_star,
