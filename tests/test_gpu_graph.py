@@ -103,11 +103,9 @@ def test_list_calls_replay_from_a_graph():
             assert torch.equal(got[k], eager[k]), f"replay {rep}: {k}"
         for a, b in zip(gq, eq):
             assert torch.equal(a, b), f"replay {rep}: quantizer output"
-    w = np.concatenate([t.cpu().numpy().reshape(-1) for t in tensors])
     go = 0
     for t in tensors:
         r = R.search(t.cpu().numpy(), 4, 50, synth.PER_CHANNEL, want_curve=True)
         C = t.shape[0]
         assert_search_matches({k: v[go:go + C].cpu().numpy() for k, v in got.items()}, r, "list graph replay")
         go += C
-    del w
