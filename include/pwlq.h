@@ -233,7 +233,7 @@ int pwlq_mse_list(const pwlq_tensor_desc *desc, int n_tensors, int bits, int mod
  * Section 4.
  *   y    device [M, N] binary32, row-major
  *   acc  device [3, M, N] int32 receiving A1, A2, A3, or NULL
- * Requirements: K a multiple of 64; xq and packed_codes 16-byte aligned,
+ * Requirements: K a multiple of 16; xq and packed_codes 16-byte aligned,
  * packed_flags 2-byte aligned; K * 128 * L below 2^31.  Workspace: device,
  * 256-byte aligned, pwlq_linear_workspace_bytes(N) bytes.
  */

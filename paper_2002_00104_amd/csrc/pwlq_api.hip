@@ -529,7 +529,7 @@ int run_linear(const int8_t *xq, int64_t M, int64_t K, float s_x, float z_x,
         return fail(PWLQ_ENULL, "an input or output pointer is NULL");
     if (M < 1 || N < 1 || K < 1) return fail(PWLQ_EINVAL, "M=%lld N=%lld K=%lld must be >= 1",
                                              (long long)M, (long long)N, (long long)K);
-    if (K % kLinBK != 0) return fail(PWLQ_EINVAL, "K=%lld is not a multiple of %d", (long long)K, kLinBK);
+    if (K % 16 != 0) return fail(PWLQ_EINVAL, "K=%lld is not a multiple of 16", (long long)K);
     if (M > (1LL << 31) / 4 || N > (1LL << 31) / 4 || K > (1LL << 22))
         return fail(PWLQ_EINVAL, "matrix too large");
     if ((((uintptr_t)xq) | ((uintptr_t)packed_codes)) & 15)

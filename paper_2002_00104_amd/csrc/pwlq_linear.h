@@ -204,24 +204,28 @@ struct LinStage {
 // channels past N read the last valid row / channel instead (their products are
 // never written), so no load sits under a branch and the compiler can count the
 // outstanding loads exactly.
+// kvalid: how many of the step's four 16-element pieces lie below K (4 except in
+// the last step when K is not a multiple of 64); the others read the step's first
+// piece instead and are zeroed when the step is written to LDS.
 template <int kBits>
 __device__ inline void lin_load(LinStage<kBits> &st, const int8_t *__restrict__ xq, long long M,
                                 long long K, const uint8_t *__restrict__ pcodes,
                                 const uint8_t *__restrict__ pflags, long long N, long long row0,
-                                long long col0, long long k0)
+                                long long col0, long long k0, int kvalid)
 {
     static_assert(kLinWG == 4 * kLinBN, "every thread carries 16 weights of the tile");
     const int t = threadIdx.x;
+    const int c = ((t & 3) < kvalid) ? (t & 3) : 0;     // piece & 3 == t & 3: kLinWG is a multiple of 4
 #pragma unroll
     for (int v = 0; v < kLinAVec; ++v) {
         const int piece = t + v * kLinWG;              // 4 pieces of 16 bytes per row
         long long r = row0 + (piece >> 2);
         r = r < M ? r : M - 1;
-        st.a[v] = *reinterpret_cast<const v4i *>(xq + r * K + k0 + (piece & 3) * 16);
+        st.a[v] = *reinterpret_cast<const v4i *>(xq + r * K + k0 + c * 16);
     }
     long long n = col0 + (t >> 2);
     n = n < N ? n : N - 1;
-    const long long e0 = n * K + k0 + (t & 3) * 16;
+    const long long e0 = n * K + k0 + c * 16;
     load_raw16<kBits>(pcodes, e0, st.codes);
     st.flags = *reinterpret_cast<const uint16_t *>(pflags + (e0 >> 3));
 }
@@ -230,14 +234,17 @@ __device__ inline void lin_load(LinStage<kBits> &st, const int8_t *__restrict__ 
 // three planes.
 template <int kBits>
 __device__ inline void lin_store(const LinStage<kBits> &st, int8_t *__restrict__ sA,
-                                 int8_t *__restrict__ sB)
+                                 int8_t *__restrict__ sB, int kvalid)
 {
     const int t = threadIdx.x;
+    const int keep = ((t & 3) < kvalid) ? -1 : 0;       // all ones for a piece below K
 #pragma unroll
     for (int v = 0; v < kLinAVec; ++v) {
         const int piece = t + v * kLinWG;
+        v4i a = st.a[v];
+        a[0] &= keep; a[1] &= keep; a[2] &= keep; a[3] &= keep;
         *reinterpret_cast<v4i *>(sA + (piece >> 2) * kLinStride +
-                                 (((piece & 3) ^ lin_swz(piece >> 2)) * 16)) = st.a[v];
+                                 (((piece & 3) ^ lin_swz(piece >> 2)) * 16)) = a;
     }
     uint32_t c[4];
     unpack16<kBits>(st.codes, c);
@@ -246,9 +253,9 @@ __device__ inline void lin_store(const LinStage<kBits> &st, int8_t *__restrict__
     for (int x = 0; x < 4; ++x) {
         uint32_t a, b, d;
         planes4(c[x], st.flags >> (4 * x), kBits, a, b, d);
-        w1[x] = (int)a;
-        w2[x] = (int)b;
-        w3[x] = (int)d;
+        w1[x] = (int)a & keep;
+        w2[x] = (int)b & keep;
+        w3[x] = (int)d & keep;
     }
     const int off = (t >> 2) * kLinStride + (((t & 3) ^ lin_swz(t >> 2)) * 16);
     *reinterpret_cast<v4i *>(sB + off) = w1;
@@ -260,7 +267,7 @@ __device__ inline void lin_store(const LinStage<kBits> &st, int8_t *__restrict__
 // step decoded into the other buffer (kStore), 6 * kLinMT matrix instructions,
 // one barrier.
 template <int kBits, bool kStore>
-__device__ inline void lin_step(v16i (&acc)[kLinMT][3], const LinStage<kBits> &next,
+__device__ inline void lin_step(v16i (&acc)[kLinMT][3], const LinStage<kBits> &next, int kvalid_next,
                                 const int8_t *a_lane, const int8_t *b_lane, int swz, int half,
                                 int8_t *sA0, int8_t *sB0, int buf)
 {
@@ -278,7 +285,7 @@ __device__ inline void lin_step(v16i (&acc)[kLinMT][3], const LinStage<kBits> &n
         for (int mt = 0; mt < kLinMT; ++mt)
             af[ks][mt] = *reinterpret_cast<const v4i *>(a_base + mt * 32 * kLinStride + chunk);
     }
-    if (kStore) lin_store<kBits>(next, sA0 + (buf ^ 1) * kABuf, sB0 + (buf ^ 1) * kBBuf);
+    if (kStore) lin_store<kBits>(next, sA0 + (buf ^ 1) * kABuf, sB0 + (buf ^ 1) * kBBuf, kvalid_next);
 #pragma unroll
     for (int ks = 0; ks < kLinBK / 32; ++ks)
 #pragma unroll
@@ -333,11 +340,14 @@ __global__ __launch_bounds__(kLinWG) void k_linear(const int8_t *__restrict__ xq
 #pragma unroll
             for (int c = 0; c < 16; ++c) acc[a][b][c] = 0;
 
-    const int steps = (int)(K / kLinBK);
+    // K is a multiple of 16; the last step holds 1 to 4 pieces of 16 elements
+    const int steps = (int)((K + kLinBK - 1) / kLinBK);
+    const int last_valid = (int)((K - (long long)(steps - 1) * kLinBK) / 16);
+    auto valid = [&](int step) { return step == steps - 1 ? last_valid : 4; };
     LinStage<kBits> near, far;
-    lin_load<kBits>(near, xq, M, K, pcodes, pflags, N, row0, col0, 0);
-    lin_store<kBits>(near, sA[0], sB[0]);
-    if (steps > 1) lin_load<kBits>(near, xq, M, K, pcodes, pflags, N, row0, col0, kLinBK);
+    lin_load<kBits>(near, xq, M, K, pcodes, pflags, N, row0, col0, 0, valid(0));
+    lin_store<kBits>(near, sA[0], sB[0], valid(0));
+    if (steps > 1) lin_load<kBits>(near, xq, M, K, pcodes, pflags, N, row0, col0, kLinBK, valid(1));
     __syncthreads();
     // row of this lane's fragments (every 32-row tile of a wavefront has the same
     // swizzle: tiles start at multiples of 32 rows) and its chunk swizzle
@@ -348,15 +358,16 @@ __global__ __launch_bounds__(kLinWG) void k_linear(const int8_t *__restrict__ xq
     // the steady-state body is free of branches
     int kt = 0;
     for (; kt + 2 < steps; ++kt) {
-        lin_load<kBits>(far, xq, M, K, pcodes, pflags, N, row0, col0, (long long)(kt + 2) * kLinBK);
-        lin_step<kBits, true>(acc, near, a_lane, b_lane, swz, half, sA[0], sB[0], kt & 1);
+        lin_load<kBits>(far, xq, M, K, pcodes, pflags, N, row0, col0, (long long)(kt + 2) * kLinBK,
+                        valid(kt + 2));
+        lin_step<kBits, true>(acc, near, valid(kt + 1), a_lane, b_lane, swz, half, sA[0], sB[0], kt & 1);
         near = far;
     }
     if (kt + 1 < steps) {
-        lin_step<kBits, true>(acc, near, a_lane, b_lane, swz, half, sA[0], sB[0], kt & 1);
+        lin_step<kBits, true>(acc, near, valid(kt + 1), a_lane, b_lane, swz, half, sA[0], sB[0], kt & 1);
         ++kt;
     }
-    lin_step<kBits, false>(acc, near, a_lane, b_lane, swz, half, sA[0], sB[0], kt & 1);
+    lin_step<kBits, false>(acc, near, 4, a_lane, b_lane, swz, half, sA[0], sB[0], kt & 1);
 
     // epilogue: C2 A1 + C4 A2 + C5 A3 + (C3 + C6), per output channel
     const long long n = col0 + wn * 32 + (lane & 31);

@@ -123,7 +123,7 @@ def test_wider_entry_points_reject_bad_arguments_on_the_host(lib):
         a.update(kw)
         return lib.pwlq_linear_i8(*[a[n] for n in names])
 
-    assert call(K=100) == 1                       # K must be a multiple of 64
+    assert call(K=100) == 1                       # K must be a multiple of 16
     assert call(bits=1) == 1
     assert call(M=0) == 1
     assert call(xq=None) == 2

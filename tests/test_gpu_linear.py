@@ -61,6 +61,13 @@ def test_shapes_b4(P, M, K, N):
     case(P, M, K, N, 4, seed=M + K + N)
 
 
+@pytest.mark.parametrize("M,K,N,bits", [(3, 16, 2, 4), (40, 48, 33, 4), (70, 80, 64, 3), (200, 144, 96, 4),
+                                         (33, 1040, 65, 5), (64, 2000, 70, 8), (10, 96, 5, 2)])
+def test_reduction_lengths_that_are_not_multiples_of_64(P, M, K, N, bits):
+    """K is a multiple of 16: the last step of the reduction holds 1, 2 or 3 pieces of 16."""
+    case(P, M, K, N, bits, seed=M * K + N)
+
+
 @pytest.mark.parametrize("bits", [2, 3, 5, 6, 7, 8])
 def test_bit_widths(P, bits):
     case(P, 70, 256, 90, bits, seed=bits, dist="normal")
@@ -75,11 +82,11 @@ def test_transformer_shape_sampled(P):
 
 def test_linear_error_statuses(P):
     import torch
-    x = torch.zeros((4, 96), dtype=torch.int8, device="cuda")
+    x = torch.zeros((4, 100), dtype=torch.int8, device="cuda")
     c = torch.zeros(1024, dtype=torch.uint8, device="cuda")
     p = torch.ones(4, device="cuda")
     with pytest.raises(P.PwlqError) as e:
-        P.linear_i8(x, 1.0, 0.0, c, c, 4, 4, p, p)            # K not a multiple of 64
+        P.linear_i8(x, 1.0, 0.0, c, c, 4, 4, p, p)            # K not a multiple of 16
     assert e.value.status == 1
     x = torch.zeros((4, 128), dtype=torch.int8, device="cuda")
     with pytest.raises(P.PwlqError) as e:
