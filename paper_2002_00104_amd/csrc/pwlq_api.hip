@@ -345,9 +345,9 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
         while (tcap < kFastTMax && 2 * tcap <= longest_fast) tcap <<= 1;
         const size_t lds = sizeof(double) * (size_t)(tcap + 1 + tcap / kFastP2Step + 1) +
                            sizeof(unsigned short) * (size_t)(tcap + 2) +
-                           sizeof(float) * (size_t)longest_fast;
+                           sizeof(float) * (size_t)(longest_fast + kFastWalkSq);
         static_assert(sizeof(double) * (kFastTMax + 1 + kFastTMax / kFastP2Step + 1) +
-                          sizeof(unsigned short) * (kFastTMax + 2) + sizeof(float) * kTileMax <=
+                          sizeof(unsigned short) * (kFastTMax + 2) + sizeof(float) * (kTileMax + kFastWalkSq) <=
                       64 * 1024, "k_fast must fit the LDS a launch gets without asking for more");
         profile_mark(4, stream);
         k_fast<<<fast_tiles, kFastWG, lds, stream>>>(tb, n_cand, bits, tcap, tile_max, gm, sse32);

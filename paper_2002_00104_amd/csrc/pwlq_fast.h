@@ -69,18 +69,29 @@ struct FastLds {
 };
 
 // Elements with u <= b: count and sum of u.  Every element of an earlier
-// bucket is below b, every element of a later bucket above.
+// bucket is below b, every element of a later bucket above.  The boundary's own
+// bucket is walked four elements at a time (the reads of a step are in flight
+// together; the array has four spare words behind the tile, and what is read
+// past the bucket's end is masked by position).
+constexpr int kFastWalk = 2;          // elements per step of a bucket walk
+constexpr int kFastWalkSq = 4;        // ... of the walk for the sum of squares, which spans up to kFastP2Step buckets
+
 __device__ inline void fast_query(const FastLds &L, float b, int &count, double &s1)
 {
     const int c = fast_bucket(b, L.shift, L.base);
     const int st = L.start[c], en = L.start[c + 1];
     int nn = st;
     double a1 = L.P1[c];
-    for (int i = st; i < en; ++i) {
-        const float u = L.elems[i];
-        const bool le = u <= b;
-        nn += le ? 1 : 0;
-        a1 += le ? (double)u : 0.0;
+    for (int i = st; i < en; i += kFastWalk) {
+        float u[kFastWalk];
+#pragma unroll
+        for (int x = 0; x < kFastWalk; ++x) u[x] = L.elems[i + x];
+#pragma unroll
+        for (int x = 0; x < kFastWalk; ++x) {
+            const bool le = (i + x < en) && (u[x] <= b);
+            nn += le ? 1 : 0;
+            a1 += le ? (double)u[x] : 0.0;
+        }
     }
     count = nn;
     s1 = a1;
@@ -97,11 +108,15 @@ __device__ inline void fast_query_squares(const FastLds &L, float b, int &count,
     int nn = st;
     double a1 = L.P1[c0];
     double a2 = L.P2[c0 / kFastP2Step];
-    for (int i = st; i < en; ++i) {
-        const float u = L.elems[i];
-        if (u <= b) {
-            const double d = (double)u;
-            ++nn;
+    for (int i = st; i < en; i += kFastWalkSq) {
+        float u[kFastWalkSq];
+#pragma unroll
+        for (int x = 0; x < kFastWalkSq; ++x) u[x] = L.elems[i + x];
+#pragma unroll
+        for (int x = 0; x < kFastWalkSq; ++x) {
+            const bool le = (i + x < en) && (u[x] <= b);
+            const double d = le ? (double)u[x] : 0.0;
+            nn += le ? 1 : 0;
             a1 += d;
             a2 += d * d;
         }
