@@ -342,7 +342,7 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
     if (fast_tiles > 0) {
         // tensors are ordered longest tile first, so the fast tiles are 0 .. fast_tiles-1
         int tcap = 64;
-        while (tcap < kFastTMax && 2 * tcap <= longest_fast) tcap <<= 1;
+        while (tcap < kFastTMax && tcap <= 2 * longest_fast) tcap <<= 1;
         const size_t lds = sizeof(double) * (size_t)(tcap + 1 + tcap / kFastP2Step + 1) +
                            sizeof(unsigned short) * (size_t)(tcap + 2) +
                            sizeof(float) * (size_t)(longest_fast + kFastWalkSq);

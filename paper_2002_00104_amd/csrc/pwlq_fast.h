@@ -90,7 +90,7 @@ __device__ inline void fast_query(const FastLds &L, float b, int &count, double 
         for (int x = 0; x < kFastWalk; ++x) {
             const bool le = (i + x < en) && (u[x] <= b);
             nn += le ? 1 : 0;
-            a1 += le ? (double)u[x] : 0.0;
+            a1 += (double)(le ? u[x] : 0.0f);
         }
     }
     count = nn;
@@ -115,7 +115,7 @@ __device__ inline void fast_query_squares(const FastLds &L, float b, int &count,
 #pragma unroll
         for (int x = 0; x < kFastWalkSq; ++x) {
             const bool le = (i + x < en) && (u[x] <= b);
-            const double d = le ? (double)u[x] : 0.0;
+            const double d = (double)(le ? u[x] : 0.0f);
             nn += le ? 1 : 0;
             a1 += d;
             a2 += d * d;
@@ -138,11 +138,13 @@ __device__ inline void fast_candidates(const FastLds &Q, int n, int len, int Li,
         int sumN = 0;          // at most L^2 K < 2^31
         int cn;
         double c1;
-        const double half_c = kd / (2.0 * Ld);
+        // half-way points in binary32: an element within a rounding of one is as far from
+        // the level below as from the level above
+        const float half_c = (float)(kd / (2.0 * Ld));
         for (int j = 0; j < Li; ++j) {
-            fast_query(Q, (float)((double)(2 * j + 1) * half_c), cn, c1);
+            fast_query(Q, (float)(2 * j + 1) * half_c, cn, c1);
             sumC += c1;
-            sumN += (2 * j + 1) * cn;
+            sumN += __mul24(2 * j + 1, cn);
         }
         int nL;
         double cL, s2L;
@@ -153,14 +155,15 @@ __device__ inline void fast_candidates(const FastLds &Q, int n, int len, int Li,
         if (k < n) {
             // tail piece: offset k, step (n-k)/L, values v = u - k
             const double wd = (double)(n - k);
-            const double half_t = wd / (2.0 * Ld);
+            const float half_t = (float)(wd / (2.0 * Ld));
+            const float kf = (float)k;
             double sumCt = 0.0;
             int sumNt = 0;
             for (int j = 0; j < Li; ++j) {
-                fast_query(Q, (float)(kd + (double)(2 * j + 1) * half_t), cn, c1);
+                fast_query(Q, __builtin_fmaf((float)(2 * j + 1), half_t, kf), cn, c1);
                 const int nt = cn - nL;
                 sumCt += (c1 - cL) - kd * (double)nt;
-                sumNt += (2 * j + 1) * nt;
+                sumNt += __mul24(2 * j + 1, nt);
             }
             const int ntL = len - nL;
             const double ctL = (S1tot - cL) - kd * (double)ntL;
@@ -237,7 +240,7 @@ __global__ __launch_bounds__(kFastWG) void k_fast(Tables tb, int n, int bits, in
     float *elems = reinterpret_cast<float *>(start + (tcap + 2));
 
     int T = 64;
-    while (T < tcap && 2 * T <= len) T <<= 1;
+    while (T < tcap && T <= 2 * len) T <<= 1;
 
     float a[kFastPer];
 #pragma unroll
