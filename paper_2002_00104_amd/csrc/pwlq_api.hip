@@ -343,14 +343,24 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
         // tensors are ordered longest tile first, so the fast tiles are 0 .. fast_tiles-1
         int tcap = 64;
         while (tcap < kFastTMax && tcap <= 2 * longest_fast) tcap <<= 1;
-        const size_t lds = sizeof(double) * (size_t)(tcap + 1 + tcap / kFastP2Step + 1) +
-                           sizeof(unsigned short) * (size_t)(tcap + 2) +
-                           sizeof(float) * (size_t)(longest_fast + kFastWalkSq);
-        static_assert(sizeof(double) * (kFastTMax + 1 + kFastTMax / kFastP2Step + 1) +
+        auto lds_bytes = [&](int p2_shift) {
+            return sizeof(double) * (size_t)(tcap + 1 + (tcap >> p2_shift) + 1) +
+                   sizeof(unsigned short) * (size_t)(tcap + 2) +
+                   sizeof(float) * (size_t)(longest_fast + kFastWalkSq);
+        };
+        static_assert(sizeof(double) * (kFastTMax + 1 + (kFastTMax >> kFastP2ShiftMax) + 1) +
                           sizeof(unsigned short) * (kFastTMax + 2) + sizeof(float) * (kTileMax + kFastWalkSq) <=
                       64 * 1024, "k_fast must fit the LDS a launch gets without asking for more");
+        // the finer prefix of squares shortens a walk; taken unless it costs a workgroup per CU
+        // (160 KB of LDS per CU, 256 bytes of static LDS per workgroup)
+        auto per_cu = [](size_t bytes) { return (size_t)(160 * 1024) / (bytes + 256); };
+        int p2_shift = kFastP2ShiftMax;
+        while (p2_shift > kFastP2ShiftMin && lds_bytes(p2_shift - 1) <= 64 * 1024 &&
+               per_cu(lds_bytes(p2_shift - 1)) == per_cu(lds_bytes(kFastP2ShiftMax)))
+            --p2_shift;
+        const size_t lds = lds_bytes(p2_shift);
         profile_mark(4, stream);
-        k_fast<<<fast_tiles, kFastWG, lds, stream>>>(tb, n_cand, bits, tcap, tile_max, gm, sse32);
+        k_fast<<<fast_tiles, kFastWG, lds, stream>>>(tb, n_cand, bits, tcap, p2_shift, tile_max, gm, sse32);
         profile_mark(5, stream);
     }
     // tiles of at most kSmallTile elements (a suffix of the tile order) get one wavefront each

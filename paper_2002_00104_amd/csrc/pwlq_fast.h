@@ -58,14 +58,16 @@ __device__ inline double wave_scan_incl_f64(double v)
     return v;
 }
 
-constexpr int kFastP2Step = 8;     // buckets per entry of the prefix of squares
+constexpr int kFastP2ShiftMin = 1, kFastP2ShiftMax = 3;   // 2, 4 or 8 buckets per entry of the prefix of squares:
+                                                          // as fine as costs no workgroup per CU
 
 struct FastLds {
     const unsigned short *start;   // [T+1] first element of each bucket
     const double *P1;              // [T+1] sum of u over the buckets before
-    const double *P2;              // [T/kFastP2Step+1] sum of u^2 before every kFastP2Step-th bucket
+    const double *P2;              // [(T >> p2_shift) + 1] sum of u^2 before every (1 << p2_shift)-th bucket
     const float *elems;            // grouped by bucket
     int shift, base;
+    int p2_shift;
 };
 
 // Elements with u <= b: count and sum of u.  Every element of an earlier
@@ -74,7 +76,7 @@ struct FastLds {
 // together; the array has four spare words behind the tile, and what is read
 // past the bucket's end is masked by position).
 constexpr int kFastWalk = 2;          // elements per step of a bucket walk
-constexpr int kFastWalkSq = 4;        // ... of the walk for the sum of squares, which spans up to kFastP2Step buckets
+constexpr int kFastWalkSq = 4;        // ... of the walk for the sum of squares, which spans several buckets
 
 __device__ inline void fast_query(const FastLds &L, float b, int &count, double &s1)
 {
@@ -97,17 +99,17 @@ __device__ inline void fast_query(const FastLds &L, float b, int &count, double 
     s1 = a1;
 }
 
-// The same with the sum of squares, which is kept per kFastP2Step buckets (it
+// The same with the sum of squares, which is kept per 2, 4 or 8 buckets (it
 // is needed once per candidate): the walk starts at that coarser boundary.
 __device__ inline void fast_query_squares(const FastLds &L, float b, int &count, double &s1,
                                           double &s2)
 {
     const int c = fast_bucket(b, L.shift, L.base);
-    const int c0 = c & ~(kFastP2Step - 1);
+    const int c0 = (c >> L.p2_shift) << L.p2_shift;
     const int st = L.start[c0], en = L.start[c + 1];
     int nn = st;
     double a1 = L.P1[c0];
-    double a2 = L.P2[c0 / kFastP2Step];
+    double a2 = L.P2[c0 >> L.p2_shift];
     for (int i = st; i < en; i += kFastWalkSq) {
         float u[kFastWalkSq];
 #pragma unroll
@@ -208,13 +210,13 @@ __device__ inline void fast_plain(const float *__restrict__ elems, int len, int 
     }
 }
 
-__global__ __launch_bounds__(kFastWG) void k_fast(Tables tb, int n, int bits, int tcap,
+__global__ __launch_bounds__(kFastWG) void k_fast(Tables tb, int n, int bits, int tcap, int p2_shift,
                                                   const float *__restrict__ tile_max,
                                                   float *__restrict__ gm,
                                                   float *__restrict__ sse32)
 {
     // dynamic LDS: P1[tcap+1] (binary64; its space first serves as the histogram
-    // and scatter cursor), P2[tcap/kFastP2Step+1], start[tcap+2] (16-bit), then
+    // and scatter cursor), P2[(tcap >> p2_shift) + 1], start[tcap+2] (16-bit), then
     // the grouped elements
     extern __shared__ double fast_lds[];
     __shared__ float redm[kFastWaves];
@@ -236,7 +238,7 @@ __global__ __launch_bounds__(kFastWG) void k_fast(Tables tb, int n, int bits, in
     double *P2 = fast_lds + (tcap + 1);
     int *cnt = reinterpret_cast<int *>(P1);
     unsigned short *start =
-        reinterpret_cast<unsigned short *>(fast_lds + (tcap + 1) + (tcap / kFastP2Step + 1));
+        reinterpret_cast<unsigned short *>(fast_lds + (tcap + 1) + ((tcap >> p2_shift) + 1));
     float *elems = reinterpret_cast<float *>(start + (tcap + 2));
 
     int T = 64;
@@ -369,10 +371,10 @@ __global__ __launch_bounds__(kFastWG) void k_fast(Tables tb, int n, int bits, in
             const int c = lo + x;
             if (c < hi) {
                 P1[c] = o1 + b1[x];
-                if ((c & (kFastP2Step - 1)) == 0) P2[c / kFastP2Step] = o2 + b2[x];
+                if ((c & ((1 << p2_shift) - 1)) == 0) P2[c >> p2_shift] = o2 + b2[x];
             }
         }
-        if (tid == kFastWG - 1) { P1[T] = o1 + t1; P2[T / kFastP2Step] = o2 + t2; }
+        if (tid == kFastWG - 1) { P1[T] = o1 + t1; P2[T >> p2_shift] = o2 + t2; }
     }
     __syncthreads();
 
@@ -383,7 +385,8 @@ __global__ __launch_bounds__(kFastWG) void k_fast(Tables tb, int n, int bits, in
     Q.elems = elems;
     Q.shift = shift;
     Q.base = base;
-    fast_candidates(Q, n, len, (1 << (bits - 1)) - 1, P1[T], P2[T / kFastP2Step],
+    Q.p2_shift = p2_shift;
+    fast_candidates(Q, n, len, (1 << (bits - 1)) - 1, P1[T], P2[T >> p2_shift],
                     sse32 + (long long)t * n);
 }
 
