@@ -341,26 +341,57 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
     }
     if (fast_tiles > 0) {
         // tensors are ordered longest tile first, so the fast tiles are 0 .. fast_tiles-1
-        int tcap = 64;
-        while (tcap < kFastTMax && tcap <= 2 * longest_fast) tcap <<= 1;
-        auto lds_bytes = [&](int p2_shift) {
-            return sizeof(double) * (size_t)(tcap + 1 + (tcap >> p2_shift) + 1) +
-                   sizeof(unsigned short) * (size_t)(tcap + 2) +
-                   sizeof(float) * (size_t)(longest_fast + kFastWalkSq);
-        };
         static_assert(sizeof(double) * (kFastTMax + 1 + (kFastTMax >> kFastP2ShiftMax) + 1) +
                           sizeof(unsigned short) * (kFastTMax + 2) + sizeof(float) * (kTileMax + kFastWalkSq) <=
                       64 * 1024, "k_fast must fit the LDS a launch gets without asking for more");
-        // the finer prefix of squares shortens a walk; taken unless it costs a workgroup per CU
-        // (160 KB of LDS per CU, 256 bytes of static LDS per workgroup)
-        auto per_cu = [](size_t bytes) { return (size_t)(160 * 1024) / (bytes + 256); };
-        int p2_shift = kFastP2ShiftMax;
-        while (p2_shift > kFastP2ShiftMin && lds_bytes(p2_shift - 1) <= 64 * 1024 &&
-               per_cu(lds_bytes(p2_shift - 1)) == per_cu(lds_bytes(kFastP2ShiftMax)))
-            --p2_shift;
-        const size_t lds = lds_bytes(p2_shift);
+        auto tcap_of = [](int longest_len) {
+            int tcap = 64;
+            while (tcap < kFastTMax && tcap <= 2 * longest_len) tcap <<= 1;
+            return tcap;
+        };
+        auto lds_bytes = [&](int longest_len, int p2_shift) {
+            const int tcap = tcap_of(longest_len);
+            return sizeof(double) * (size_t)(tcap + 1 + (tcap >> p2_shift) + 1) +
+                   sizeof(unsigned short) * (size_t)(tcap + 2) +
+                   sizeof(float) * (size_t)(longest_len + kFastWalkSq);
+        };
+        // workgroups of a launch per CU: 160 KB of LDS (256 bytes of it static per workgroup),
+        // 32 wavefront slots
+        auto per_cu = [](size_t bytes) {
+            return std::min((size_t)(32 / kFastWaves), (size_t)(160 * 1024) / (bytes + 256));
+        };
+        // A launch's LDS is sized for its longest tile.  When the longest tiles keep the others
+        // from a fourth workgroup per CU, they get a launch of their own.
+        int split = 0;          // tiles of the first launch; 0: one launch
+        {
+            int seen = 0, first_full = -1;
+            for (const TensorRec &r : pl.recs) {
+                if (!r.fast) break;
+                if (first_full < 0 && per_cu(lds_bytes(r.tile_len, kFastP2ShiftMax)) >
+                                          per_cu(lds_bytes(longest_fast, kFastP2ShiftMax)))
+                    first_full = seen;
+                seen += r.ntiles;
+            }
+            if (first_full >= 1024 && fast_tiles - first_full >= 1024) split = first_full;
+        }
         profile_mark(4, stream);
-        k_fast<<<fast_tiles, kFastWG, lds, stream>>>(tb, n_cand, bits, tcap, p2_shift, tile_max, gm, sse32);
+        for (int part = 0; part < (split ? 2 : 1); ++part) {
+            const int begin = part ? split : 0;
+            const int count = split ? (part ? fast_tiles - split : split) : fast_tiles;
+            int part_longest = 0, seen = 0;
+            for (const TensorRec &r : pl.recs) {
+                if (!r.fast) break;
+                if (seen >= begin && seen < begin + count) part_longest = std::max(part_longest, r.tile_len);
+                seen += r.ntiles;
+            }
+            // the finer prefix of squares shortens a walk; taken unless it costs a workgroup per CU
+            int p2_shift = kFastP2ShiftMax;
+            while (p2_shift > kFastP2ShiftMin && lds_bytes(part_longest, p2_shift - 1) <= 64 * 1024 &&
+                   per_cu(lds_bytes(part_longest, p2_shift - 1)) == per_cu(lds_bytes(part_longest, kFastP2ShiftMax)))
+                --p2_shift;
+            k_fast<<<count, kFastWG, lds_bytes(part_longest, p2_shift), stream>>>(
+                tb, begin, n_cand, bits, tcap_of(part_longest), p2_shift, tile_max, gm, sse32);
+        }
         profile_mark(5, stream);
     }
     // tiles of at most kSmallTile elements (a suffix of the tile order) get one wavefront each

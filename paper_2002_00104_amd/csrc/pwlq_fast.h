@@ -210,7 +210,7 @@ __device__ inline void fast_plain(const float *__restrict__ elems, int len, int 
     }
 }
 
-__global__ __launch_bounds__(kFastWG) void k_fast(Tables tb, int n, int bits, int tcap, int p2_shift,
+__global__ __launch_bounds__(kFastWG) void k_fast(Tables tb, int tile_begin, int n, int bits, int tcap, int p2_shift,
                                                   const float *__restrict__ tile_max,
                                                   float *__restrict__ gm,
                                                   float *__restrict__ sse32)
@@ -230,7 +230,7 @@ __global__ __launch_bounds__(kFastWG) void k_fast(Tables tb, int n, int bits, in
     const int lane = tid & 63;
     const int wave = tid >> 6;
     TensorRec r;
-    TileInfo ti = tile_of(tb, blockIdx.x, r, t);
+    TileInfo ti = tile_of(tb, tile_begin + blockIdx.x, r, t);
     if (!r.fast) return;
     const int len = ti.len;
 
