@@ -1,9 +1,8 @@
 """GPU parity: the HIP library against the CPU oracle on the same seeded inputs.
 
-All calls go through the C ABI (ctypes binding).  Small cases are compared
-group by group and element by element; the full-size workloads run on the GPU
-in the benchmark's launch configuration and are compared on sampled groups the
-oracle can compute one by one.
+All calls go through the C ABI (ctypes binding).  Every case, the five
+workloads at full size in the benchmark's launch configuration included, is
+compared group by group and element by element.
 """
 import sys
 
@@ -205,9 +204,17 @@ def test_repeatable(P):
 
 
 # ------------------------------------------------------------- model-level calls
-def _list_case(P, tensors, bits, n, mode, what, check_groups=None):
-    """Runs search_list + quantize_list on the GPU over all tensors and checks
-    the tensors / groups named in check_groups (default: everything)."""
+def _merge(total, stats):
+    total["groups"] += stats["groups"]
+    total["undecided"] += stats["undecided"]
+    total["max_mse_rel"] = max(total["max_mse_rel"], stats["max_mse_rel"])
+
+
+def _list_case(P, tensors, bits, n, mode, what, check_groups=None, packed=False):
+    """Runs search_list (exhaustive and fast) and quantize_list (and, with
+    `packed`, quantize_packed_list) on the GPU over all tensors in one set of
+    launches and compares them with the oracle: every group and every element
+    of every tensor, or only the tensors / rows named in check_groups."""
     import torch
     say(f"[case] {what}: {len(tensors)} tensors bits={bits} n={n} mode={mode}")
     dev = [torch.from_numpy(t).cuda() for t in tensors]
@@ -221,80 +228,77 @@ def _list_case(P, tensors, bits, n, mode, what, check_groups=None):
     codes, flags, w_hat = P.quantize_list(tl, bits, out["p_star"], out["m"])
     torch.cuda.synchronize()
     say("  quantize done")
+    if packed:
+        pc, pf, _, layout = P.quantize_packed_list(tl, bits, out["p_star"], out["m"])
+        torch.cuda.synchronize()
+        pc, pf = pc.cpu().numpy(), pf.cpu().numpy()
+        say("  packed quantize done")
     g = to_np(out)
+    total = dict(groups=0, undecided=0, max_mse_rel=0.0, elements=0)
+    total_fast = dict(groups=0, undecided=0, max_mse_rel=0.0)
     todo = check_groups if check_groups is not None else {i: None for i in range(len(tensors))}
     for ti, rows in todo.items():
         w = tensors[ti]
         go, eo = tl.group_offsets[ti], tl.elem_offsets[ti]
         C, K = w.shape
+        whole = mode == synth.PER_TENSOR or rows is None
         if mode == synth.PER_TENSOR:
-            r = R.search(w, bits, n, mode, want_curve=True)
-            gs = {k: v[go:go + 1] for k, v in g.items()}
-            assert_search_matches(gs, r, f"{what} tensor {ti}")
-            assert_search_matches({k: v[go:go + 1] for k, v in fast.items()}, r,
-                                  f"{what} tensor {ti} (fast)")
-            sl = slice(eo, eo + C * K)
-            got = tuple(t[sl].cpu().numpy().reshape(C, K) for t in (codes, flags, w_hat))
-            want = R.quantize(w, bits, gs["p_star"], gs["m"], mode)
-            assert_quantize_matches(got, want, f"{what} tensor {ti}")
+            gsel = slice(go, go + 1)
+            wsel = w
+        elif rows is None:
+            gsel = slice(go, go + C)
+            wsel = w
         else:
-            rows = np.arange(C) if rows is None else np.asarray(rows)
-            r = R.search(w[rows], bits, n, mode, want_curve=True)
-            gs = {k: v[go + rows] for k, v in g.items()}
-            assert_search_matches(gs, r, f"{what} tensor {ti}")
-            assert_search_matches({k: v[go + rows] for k, v in fast.items()}, r,
-                                  f"{what} tensor {ti} (fast)")
+            rows = np.asarray(rows)
+            gsel = go + rows
+            wsel = w[rows]
+        r = R.search(wsel, bits, n, mode, want_curve=True)
+        gs = {k: v[gsel] for k, v in g.items()}
+        _merge(total, assert_search_matches(gs, r, f"{what} tensor {ti}"))
+        _merge(total_fast, assert_search_matches({k: v[gsel] for k, v in fast.items()}, r,
+                                                 f"{what} tensor {ti} (fast)"))
+        # the quantizer is compared at the parameters the GPU search returned: its p* is
+        # bit-identical to the oracle's wherever k* agrees (checked above)
+        want = R.quantize(wsel, bits, gs["p_star"], gs["m"], mode)
+        if whole:
+            got = tuple(t[eo:eo + C * K].cpu().numpy().reshape(C, K) for t in (codes, flags, w_hat))
+        else:
             got = tuple(t[eo:eo + C * K].view(C, K)[torch.from_numpy(rows).cuda()].cpu().numpy()
                         for t in (codes, flags, w_hat))
-            want = R.quantize(w[rows], bits, gs["p_star"], gs["m"], mode)
-            assert_quantize_matches(got, want, f"{what} tensor {ti}")
-    return tl
+        assert_quantize_matches(got, want, f"{what} tensor {ti}")
+        total["elements"] += want[0].size
+        if packed and whole:
+            want_c, want_f = R.pack(want[0], want[1], bits)
+            co, fo = layout.code_off[ti], layout.flag_off[ti]
+            np.testing.assert_array_equal(pc[co:co + want_c.size], want_c,
+                                          err_msg=f"{what} tensor {ti}: packed codes")
+            np.testing.assert_array_equal(pf[fo:fo + want_f.size], want_f,
+                                          err_msg=f"{what} tensor {ti}: packed flags")
+    say(f"  [parity] {what}: exhaustive {total}; fast {total_fast}")
+    return tl, total
 
 
 def test_list_small_mixed(P):
     rng = np.random.default_rng(5)
     shapes = [(7, 9), (16, 27), (5, 4608), (3, 9000), (40, 64), (1, 1), (12, 577)]
     tensors = [rng.laplace(0, 0.04, size=s).astype(np.float32) for s in shapes]
-    _list_case(P, tensors, 4, 300, synth.PER_CHANNEL, "list mixed per-channel")
-    _list_case(P, tensors, 3, 200, synth.PER_TENSOR, "list mixed per-tensor")
+    _list_case(P, tensors, 4, 300, synth.PER_CHANNEL, "list mixed per-channel", packed=True)
+    _list_case(P, tensors, 3, 200, synth.PER_TENSOR, "list mixed per-tensor", packed=True)
 
 
-def _sample_rows(C, count, rng):
-    return np.sort(rng.choice(C, size=min(C, count), replace=False))
-
-
-def test_workload2_full_size_sampled(P):
-    wl = synth.workload(2)
+# The four model-level workloads at full size, in the launch configuration the
+# benchmark times (one search_list and one quantize_list over all tensors):
+# every group's k*, p*, m and mse from the exhaustive and from the fast search,
+# every element's code, flag and dequantized value, and the bit-packed streams,
+# against the oracle.
+@pytest.mark.parametrize("index", [2, 3, 4, 5])
+def test_workload_full_size(P, index):
+    wl = synth.workload(index)
     tensors = list(wl.tensors())
-    rng = np.random.default_rng(2)
-    check = {t: _sample_rows(tensors[t].shape[0], 6, rng) for t in range(wl.n_tensors)}
-    _list_case(P, tensors, wl.bits, wl.n_cand, wl.mode, "workload2", check)
-
-
-def test_workload3_full_size_sampled(P):
-    wl = synth.workload(3)
-    tensors = list(wl.tensors())
-    rng = np.random.default_rng(3)
-    check = {t: _sample_rows(tensors[t].shape[0], 24, rng) for t in range(wl.n_tensors)}
-    _list_case(P, tensors, wl.bits, wl.n_cand, wl.mode, "workload3", check)
-
-
-def test_workload4_full_size_sampled(P):
-    wl = synth.workload(4)
-    tensors = list(wl.tensors())
-    sizes = np.array([t.size for t in tensors])
-    order = np.argsort(sizes)
-    picks = sorted({int(order[0]), int(order[1]), int(order[len(order) // 4]),
-                    int(order[len(order) // 2]), int(order[3 * len(order) // 4]), int(order[-1])})
-    _list_case(P, tensors, wl.bits, wl.n_cand, wl.mode, "workload4", {t: None for t in picks})
-
-
-def test_workload5_full_size_sampled(P):
-    wl = synth.workload(5)
-    tensors = list(wl.tensors())
-    rng = np.random.default_rng(5)
-    check = {t: _sample_rows(tensors[t].shape[0], 12, rng) for t in range(wl.n_tensors)}
-    _list_case(P, tensors, wl.bits, wl.n_cand, wl.mode, "workload5", check)
+    _, total = _list_case(P, tensors, wl.bits, wl.n_cand, wl.mode, f"workload{index}", packed=True)
+    n_groups = sum(t.shape[0] if wl.mode == synth.PER_CHANNEL else 1 for t in tensors)
+    assert total["groups"] == n_groups                     # no group left out
+    assert total["elements"] == sum(t.size for t in tensors)
 
 
 # --------------------------------------------------------------------- ABI errors
