@@ -82,6 +82,32 @@ int pwlq_search(const float *w, int64_t C, int64_t K, int bits, int n_cand, int 
                 void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * pwlq_search for callers that cannot allocate device memory (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the
+ * same kernels, arguments and outputs as pwlq_search, with the scratch taken
+ * from a buffer of PWLQ_STATIC_SCRATCH_BYTES that is part of the library's
+ * device image (one copy per GPU, held until the process ends) instead of a
+ * caller's workspace.  The call allocates and frees nothing on the device and
+ * calls no allocating library routine.
+ *   - A search whose pwlq_search_workspace_bytes(C, K, bits, n_cand, mode)
+ *     exceeds PWLQ_STATIC_SCRATCH_BYTES returns PWLQ_EWORKSPACE and enqueues
+ *     nothing (32 MiB holds, e.g., 3000 channels of 1000 weights with 1000
+ *     candidates, or one group of 7 million weights with 100).
+ *   - The buffer belongs to the device that is current at the call, which must
+ *     be the device of `stream`.  Its address is looked up on the first call
+ *     made on a device; make that call outside stream capture.
+ *   - Every call on a GPU shares that GPU's buffer, which keeps the previous
+ *     call's contents; the kernels read nothing from it that the same call has
+ *     not written, so nothing is cleared.  Two calls that overlap in time on
+ *     one GPU (different streams, or graphs replayed concurrently) race on it:
+ *     the caller serialises them.
+ */
+#define PWLQ_STATIC_SCRATCH_BYTES (32u << 20)
+
+int pwlq_search_static(const float *w, int64_t C, int64_t K, int bits, int n_cand, int mode,
+                       float *p_star, float *m_out, int32_t *k_star, double *mse, void *stream);
+
+/*
  * The same search with the same outputs, computed with less work: for tiles
  * long enough to pay for it, a candidate's squared error is obtained from
  * cumulative counts and sums of the magnitudes (2^b - 1 look-ups per

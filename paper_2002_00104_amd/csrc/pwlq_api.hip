@@ -6,11 +6,17 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <numeric>
 #include <vector>
 
 #include "../../include/pwlq.h"
 #include "pwlq_kernels.h"
+
+// Scratch of pwlq_search_static: one copy per GPU, resident until the process
+// ends.  In host code this name is only a handle for hipGetSymbolAddress; the
+// device address it yields is what kernels and copies are given.
+static __device__ __align__(256) unsigned char scratch[PWLQ_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -612,9 +618,56 @@ int run_linear(const int8_t *xq, int64_t M, int64_t K, float s_x, float z_x,
     return launch_status("linear launch");
 }
 
+// Device address of `scratch` on the current device, looked up once per device.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(PWLQ_EHIP, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(PWLQ_EHIP, "device index %d not supported", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr)
+            return fail(PWLQ_EHIP, "hipGetSymbolAddress(scratch) on device %d: %s", dev,
+                        hipGetErrorString(e));
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return PWLQ_OK;
+}
+
 } // namespace
 
 extern "C" {
+
+int pwlq_search_static(const float *w, int64_t C, int64_t K, int bits, int n_cand, int mode,
+                       float *p_star, float *m_out, int32_t *k_star, double *mse, void *stream)
+{
+    if (!w) return fail(PWLQ_ENULL, "w is NULL");
+    int rc = check_common(bits, mode);
+    if (rc) return rc;
+    if (n_cand < 1 || n_cand > 65535) return fail(PWLQ_EINVAL, "n_cand=%d outside [1,65535]", n_cand);
+    pwlq_tensor_desc d = {w, C, K, 0, 0};
+    Plan pl;
+    rc = build_plan(pl, &d, 1, n_cand, mode, true);
+    if (rc) return rc;
+    if (pl.total > (size_t)PWLQ_STATIC_SCRATCH_BYTES)
+        return fail(PWLQ_EWORKSPACE,
+                    "this search needs %zu bytes of scratch, the library's static buffer holds %zu: "
+                    "call pwlq_search with a workspace of the caller's",
+                    pl.total, (size_t)PWLQ_STATIC_SCRATCH_BYTES);
+    void *ptr = nullptr;
+    rc = static_scratch(&ptr);
+    if (rc) return rc;
+    return run_search(&d, 1, bits, n_cand, mode, p_star, m_out, k_star, mse, ptr,
+                      (size_t)PWLQ_STATIC_SCRATCH_BYTES, stream);
+}
 
 size_t pwlq_linear_workspace_bytes(int64_t N)
 {

@@ -22,7 +22,7 @@ LIB_PATH = os.path.join(_HERE, "libpwlq.so")
 EXPORTS = (
     "pwlq_search_workspace_bytes", "pwlq_search", "pwlq_quantize",
     "pwlq_search_list_workspace_bytes", "pwlq_search_list",
-    "pwlq_search_fast", "pwlq_search_fast_list",
+    "pwlq_search_fast", "pwlq_search_fast_list", "pwlq_search_static",
     "pwlq_quantize_list_workspace_bytes", "pwlq_quantize_list",
     "pwlq_packed_code_bytes", "pwlq_packed_flag_bytes", "pwlq_quantize_packed",
     "pwlq_quantize_packed_list",
@@ -60,6 +60,8 @@ def _load() -> ctypes.CDLL:
     lib.pwlq_search.argtypes = [vp, i64, i64, ci, ci, ci, vp, vp, vp, vp, vp, sz, vp]
     lib.pwlq_search_fast.restype = ci
     lib.pwlq_search_fast.argtypes = lib.pwlq_search.argtypes
+    lib.pwlq_search_static.restype = ci
+    lib.pwlq_search_static.argtypes = [vp, i64, i64, ci, ci, ci, vp, vp, vp, vp, vp]
     lib.pwlq_quantize.restype = ci
     lib.pwlq_quantize.argtypes = [vp, i64, i64, ci, ci, vp, vp, vp, vp, vp, vp]
     lib.pwlq_search_list_workspace_bytes.restype = sz
@@ -164,6 +166,24 @@ def search(w: torch.Tensor, bits: int, n_cand: int, mode: int = PER_CHANNEL,
     _check(fn(w.data_ptr(), C, K, bits, n_cand, mode, out["p_star"].data_ptr(),
               out["m"].data_ptr(), out["k_star"].data_ptr(), out["mse"].data_ptr(),
               workspace.data_ptr(), workspace.numel(), _stream()))
+    return out
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def search_static(w: torch.Tensor, bits: int, n_cand: int, mode: int = PER_CHANNEL,
+                  out: Optional[Dict[str, torch.Tensor]] = None) -> Dict[str, torch.Tensor]:
+    """pwlq_search_static on one [C, K] tensor: the search with the library's own
+    scratch buffer.  With `out` given (see alloc_search_outputs) this binding
+    allocates nothing either."""
+    w = _dev32(w)
+    C, K = w.shape
+    if out is None:
+        out = alloc_search_outputs(_n_groups(C, mode), w.device)
+    _check(lib.pwlq_search_static(w.data_ptr(), C, K, bits, n_cand, mode, out["p_star"].data_ptr(),
+                                  out["m"].data_ptr(), out["k_star"].data_ptr(),
+                                  out["mse"].data_ptr(), _stream()))
     return out
 
 

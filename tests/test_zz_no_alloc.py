@@ -1,0 +1,86 @@
+"""pwlq_search_static (the search with the library's own scratch buffer, for
+callers that cannot allocate) against pwlq_search, through the C ABI: two calls
+in a row, the second on a smaller input, so that whatever the first call left
+in the shared buffer is there when the second runs."""
+import ctypes
+
+import numpy as np
+import pytest
+
+from oracle import pwlq_ref as R
+from paper_2002_00104_amd import synth
+from parity import assert_search_matches
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2002_00104_amd import pwlq
+    return pwlq
+
+
+def _raw_static(P, wd, bits, n, mode, out):
+    import torch
+    C, K = wd.shape
+    rc = P.lib.pwlq_search_static(wd.data_ptr(), C, K, bits, n, mode, out["p_star"].data_ptr(),
+                                  out["m"].data_ptr(), out["k_star"].data_ptr(),
+                                  out["mse"].data_ptr(), torch.cuda.current_stream().cuda_stream)
+    return rc
+
+
+def _compare(P, w, bits, n, mode, what):
+    import torch
+    print(f"[case] no-alloc {what}: shape={w.shape} bits={bits} n={n} mode={mode}", flush=True)
+    wd = torch.from_numpy(w).cuda()
+    G = w.shape[0] if mode == synth.PER_CHANNEL else 1
+    out = P.alloc_search_outputs(G, wd.device)
+    for t in out.values():
+        t.fill_(-7)                      # stale values must be overwritten
+    torch.cuda.synchronize()
+    before = torch.cuda.memory_allocated()
+    assert _raw_static(P, wd, bits, n, mode, out) == 0, P.lib.pwlq_last_error().decode()
+    torch.cuda.synchronize()
+    assert torch.cuda.memory_allocated() == before          # nothing allocated through torch
+    got = {k: v.cpu().numpy() for k, v in out.items()}
+    want = {k: v.cpu().numpy() for k, v in P.search(wd, bits, n, mode).items()}
+    for k in ("k_star", "p_star", "m", "mse"):
+        np.testing.assert_array_equal(got[k].view(np.uint8), want[k].view(np.uint8),
+                                      err_msg=f"{what}: {k} differs from pwlq_search")
+    assert_search_matches(got, R.search(w, bits, n, mode, want_curve=True), what)
+
+
+def test_static_scratch_two_calls_in_a_row(P):
+    rng = np.random.default_rng(12)
+    # first call: 3000 channels of 1000 weights, 1000 candidates: 24.6 of the 32 MiB
+    big = (rng.laplace(0, 0.03, size=(3000, 1000)) *
+           np.exp(rng.normal(0, 0.5, size=(3000, 1)))).astype(np.float32)
+    need = P.search_workspace_bytes(3000, 1000, 4, 1000, synth.PER_CHANNEL)
+    assert 0.5 * P.STATIC_SCRATCH_BYTES < need <= P.STATIC_SCRATCH_BYTES
+    _compare(P, big, 4, 1000, synth.PER_CHANNEL, "first call")
+    # second call: smaller input, other shapes of the same buffer's layout
+    wl = synth.workload(1)
+    _compare(P, wl.tensor(0), wl.bits, wl.n_cand, wl.mode, "second call (workload 1)")
+    # and a group of several tiles, per tensor, ragged tail
+    small = (0.02 * rng.standard_t(3.0, size=(3, 9001))).astype(np.float32)
+    _compare(P, small, 3, 257, synth.PER_TENSOR, "third call (per tensor)")
+
+
+def test_static_scratch_rejects_what_does_not_fit(P):
+    import torch
+    C, K, n = 8192, 1024, 2000
+    assert P.search_workspace_bytes(C, K, 4, n, synth.PER_CHANNEL) > P.STATIC_SCRATCH_BYTES
+    wd = torch.zeros((C, K), device="cuda")
+    out = P.alloc_search_outputs(C, wd.device)
+    for t in out.values():
+        t.fill_(-7)
+    assert _raw_static(P, wd, 4, n, synth.PER_CHANNEL, out) == 3          # PWLQ_EWORKSPACE
+    msg = P.lib.pwlq_last_error().decode()
+    assert "static buffer" in msg and str(P.STATIC_SCRATCH_BYTES) in msg
+    torch.cuda.synchronize()
+    assert (out["k_star"] == -7).all()                       # nothing was enqueued
+    with pytest.raises(P.PwlqError) as e:
+        P.search_static(wd, 9, n)
+    assert e.value.status == 1
