@@ -19,10 +19,15 @@
  *     tensor table into the workspace through kernel arguments) and can be
  *     recorded into a HIP graph and replayed (same pointers, new contents).
  *     Exception: a list call whose table exceeds 63 KB (about 500 tensors)
- *     copies it from host memory instead and returns PWLQ_EINVAL on a
+ *     copies it from host memory instead, waits for that copy (and so for the
+ *     work queued on `stream` before it) and returns PWLQ_EINVAL on a
  *     capturing stream.
- *   - Return value: a pwlq_status.  On any status other than PWLQ_OK nothing
- *     was enqueued and no output is written; pwlq_last_error() describes it.
+ *   - Return value: a pwlq_status; pwlq_last_error() describes a failure.
+ *     PWLQ_EINVAL, PWLQ_ENULL and PWLQ_EWORKSPACE are found before anything is
+ *     launched: nothing was enqueued and no output is written.  PWLQ_EHIP
+ *     reports a failure of the HIP runtime itself (a launch or copy it
+ *     refused); kernels of the same call launched before it may already be
+ *     queued, so the workspace and the outputs are then undefined.
  *   - Valid ranges: 2 <= bits <= 8, 1 <= n_cand <= 65535, C >= 1, K >= 1,
  *     at most 2^31-1 elements per group's tile set and per call 2^31-1 tiles.
  *   - A group whose absmax is NaN or infinite gets k_star = -1 and NaN in
@@ -273,28 +278,6 @@ int pwlq_linear_i8(const int8_t *xq, int64_t M, int64_t K, float s_x, float z_x,
 /* Text of the calling thread's last non-OK status ("" if none).  The storage
  * is thread-local and owned by the library. */
 const char *pwlq_last_error(void);
-
-/* Counters of the last pwlq_search* call enqueued by the calling thread, for
- * benchmarks: number of tiles, groups and work units.  Any pointer may be NULL. */
-void pwlq_last_search_shape(int64_t *n_tiles, int64_t *n_groups, int64_t *n_units);
-
-/* Benchmark aid.  With profiling enabled every search / quantize call records
- * HIP events on its own stream right before and after its dominant kernel
- * (role 0: the candidate-evaluation kernel of a search; role 1: the quantize
- * kernel; role 2: the prefix-sum evaluation kernel of a fast search; role 3: the
- * integer inner-product kernel).  pwlq_profile_last_ms waits for the later event of the most recent
- * call and returns the kernel's duration in milliseconds, or -1 if none was
- * recorded.  Process-wide, not thread-safe; off by default. */
-void pwlq_profile_enable(int on);
-double pwlq_profile_last_ms(int role);
-/* The same for an earlier launch of that role: back = 0 is the most recent one,
- * back = 1 the one before, up to the last 64 recorded launches; -1 beyond. */
-double pwlq_profile_ms(int role, int back);
-
-/* Name of the library's kernels as they appear in a kernel trace, by role:
- * 0 search (dominant), 1 quantize, 2 prefix-sum evaluation, 3 integer inner
- * product.  Returns NULL for other roles. */
-const char *pwlq_kernel_name(int role);
 
 #ifdef __cplusplus
 }

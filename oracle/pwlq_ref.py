@@ -23,23 +23,38 @@ PER_TENSOR = 1
 CFLAGS = ["-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
           "-shared", "-fPIC", "-Wall", "-Wextra"]
 
+# Checking configuration: the same source under AddressSanitizer and
+# UndefinedBehaviorSanitizer, in a library of its own.  A process that sets
+# PWLQ_REF_SANITIZE=1 (and preloads gcc's libasan.so) loads that one instead.
+_LIB_SAN = os.path.join(_HERE, "libpwlq_ref_san.so")
+SAN_CFLAGS = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+              "-fno-sanitize-recover=all"] + [f for f in CFLAGS if f != "-O2"]
+SANITIZE = os.environ.get("PWLQ_REF_SANITIZE") == "1"
 
-def build(force: bool = False) -> str:
+
+def build(force: bool = False, sanitize: bool = False) -> str:
     """Compile the oracle with gcc.  Returns the path of the shared object."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", *CFLAGS, _SRC, "-o", _LIB, "-lm"]
+    out, flags = (_LIB_SAN, SAN_CFLAGS) if sanitize else (_LIB, CFLAGS)
+    if force or not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(_SRC):
+        cmd = ["gcc", *flags, _SRC, "-o", out, "-lm"]
         subprocess.run(cmd, check=True)
-    return _LIB
+    return out
 
 
 _lib: Optional[ctypes.CDLL] = None
+_loaded: Optional[str] = None
+
+
+def loaded_path() -> Optional[str]:
+    """Path of the shared object this process has loaded (None before the first call)."""
+    return _loaded
 
 
 def lib() -> ctypes.CDLL:
-    global _lib
+    global _lib, _loaded
     if _lib is None:
-        build()
-        L = ctypes.CDLL(_LIB)
+        _loaded = build(sanitize=SANITIZE)
+        L = ctypes.CDLL(_loaded)
         fp = ctypes.POINTER(ctypes.c_float)
         dp = ctypes.POINTER(ctypes.c_double)
         ip = ctypes.POINTER(ctypes.c_int32)

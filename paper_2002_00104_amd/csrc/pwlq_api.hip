@@ -11,6 +11,7 @@
 #include <vector>
 
 #include "../../include/pwlq.h"
+#include "../../include/pwlq_bench.h"
 #include "pwlq_kernels.h"
 
 // Scratch of pwlq_search_static: one copy per GPU, resident until the process
@@ -202,8 +203,8 @@ int check_workspace(const Plan &pl, const void *workspace, size_t bytes)
 // Writes the tensor table into the head of the workspace and returns the
 // device-side view.  Tables of up to kUploadMaxBytes travel in the arguments of
 // k_upload launches (asynchronous, nothing on the host has to outlive the call,
-// recordable into a graph); longer ones are copied from host memory, which the
-// runtime stages before hipMemcpyAsync returns, and cannot be recorded.
+// recordable into a graph); longer ones are copied from a host image that lives
+// only for this call, so the call waits for the copy, and cannot be recorded.
 constexpr size_t kUploadMaxBytes = 16 * sizeof(UploadChunk);
 
 int upload_tables(const Plan &pl, char *ws, hipStream_t stream, Tables &tb)
@@ -243,6 +244,7 @@ int upload_tables(const Plan &pl, char *ws, hipStream_t stream, Tables &tb)
             return fail(PWLQ_EINVAL, "a call with this many tensors copies its table from host memory "
                                      "and cannot be recorded into a graph");
         hipError_t e = hipMemcpyAsync(ws + pl.off_recs, image.data(), bytes, hipMemcpyHostToDevice, stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(stream);    // `image` is gone when this function returns
         if (e != hipSuccess) return fail(PWLQ_EHIP, "table upload: %s", hipGetErrorString(e));
     }
     tb.recs = reinterpret_cast<const TensorRec *>(ws + pl.off_recs);

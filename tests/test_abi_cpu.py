@@ -9,7 +9,10 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "pwlq.h")
-LIB = os.path.join(ROOT, "paper_2002_00104_amd", "libpwlq.so")
+HEADERS = sorted(os.path.join(ROOT, "include", f) for f in os.listdir(os.path.join(ROOT, "include"))
+                 if f.endswith(".h"))
+# PWLQ_LIB: another build of the same library (the host-sanitizer configuration)
+LIB = os.environ.get("PWLQ_LIB") or os.path.join(ROOT, "paper_2002_00104_amd", "libpwlq.so")
 
 
 @pytest.fixture(scope="module")
@@ -21,7 +24,7 @@ def lib():
 
 
 def declared_functions():
-    text = open(HEADER).read()
+    text = "\n".join(open(h).read() for h in HEADERS)
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(pwlq_[a-z_]+)\s*\(", text)))
 
@@ -53,6 +56,56 @@ def test_workspace_sizes(lib):
     for bad in ((0, 5, 4, 10, 0), (5, 0, 4, 10, 0), (5, 5, 1, 10, 0), (5, 5, 9, 10, 0),
                 (5, 5, 4, 0, 0), (5, 5, 4, 70000, 0), (5, 5, 4, 10, 2)):
         assert f(*bad) == 0, bad
+
+
+class _Desc(ctypes.Structure):
+    _fields_ = [("w", ctypes.c_void_p), ("C", ctypes.c_int64), ("K", ctypes.c_int64),
+                ("group_offset", ctypes.c_int64), ("elem_offset", ctypes.c_int64)]
+
+
+def test_model_level_plans_on_the_host(lib):
+    """Tensor tables of 1 to 700 tensors of mixed shapes through every workspace query and,
+    with a NULL workspace, through the calls themselves up to the point where they refuse."""
+    import random
+    rnd = random.Random(3)
+    sz, ci, vp = ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p
+    dp = ctypes.POINTER(_Desc)
+    lib.pwlq_search_list_workspace_bytes.restype = sz
+    lib.pwlq_search_list_workspace_bytes.argtypes = [dp, ci, ci, ci, ci]
+    lib.pwlq_quantize_list_workspace_bytes.restype = sz
+    lib.pwlq_quantize_list_workspace_bytes.argtypes = [dp, ci, ci, ci]
+    lib.pwlq_select_list_workspace_bytes.restype = sz
+    lib.pwlq_select_list_workspace_bytes.argtypes = [dp, ci, ci]
+    lib.pwlq_mse_list_workspace_bytes.restype = sz
+    lib.pwlq_mse_list_workspace_bytes.argtypes = [dp, ci, ci]
+    lib.pwlq_search_list.restype = ci
+    lib.pwlq_search_list.argtypes = [dp, ci, ci, ci, ci, vp, vp, vp, vp, vp, sz, vp]
+    lib.pwlq_search_fast_list.restype = ci
+    lib.pwlq_search_fast_list.argtypes = lib.pwlq_search_list.argtypes
+    fake = 0x1000   # never dereferenced
+    for nt in (1, 2, 63, 64, 65, 700):
+        d = (_Desc * nt)()
+        g = e = 0
+        for i in range(nt):
+            C = rnd.choice((1, 3, 64, 1000))
+            K = rnd.choice((1, 9, 64, 577, 4608, 8192, 8193, 100003))
+            d[i] = _Desc(fake, C, K, g, e)
+            g += C
+            e += C * K
+        for mode in (0, 1):
+            for n in (1, 64, 1000, 2049):
+                need = lib.pwlq_search_list_workspace_bytes(d, nt, 4, n, mode)
+                assert need >= 4 * e
+                assert lib.pwlq_search_list(d, nt, 4, n, mode, fake, fake, fake, fake, None, 0, None) == 3
+                assert lib.pwlq_search_list(d, nt, 4, n, mode, fake, fake, fake, fake, fake << 8,
+                                            need - 1, None) == 3
+                assert lib.pwlq_search_fast_list(d, nt, 4, n, mode, fake, fake, fake, fake, fake << 8,
+                                                 256, None) == 3
+            assert lib.pwlq_quantize_list_workspace_bytes(d, nt, 4, mode) > 0
+            assert lib.pwlq_select_list_workspace_bytes(d, nt, mode) > 0
+            assert lib.pwlq_mse_list_workspace_bytes(d, nt, mode) > 0
+        d[nt - 1].K = 0
+        assert lib.pwlq_search_list_workspace_bytes(d, nt, 4, 100, 0) == 0
 
 
 def test_bad_arguments_are_rejected_on_the_host(lib):
@@ -153,18 +206,19 @@ def test_bench_refuses_more_than_one_gpu():
 
 
 def test_header_is_plain_c(tmp_path):
-    """include/pwlq.h compiles as C99 on its own (no HIP or C++ needed by a caller)."""
+    """Every header under include/ compiles as C99 on its own (no HIP or C++ needed by a caller)."""
     import shutil
     import subprocess
     gcc = shutil.which("gcc")
     if gcc is None:
         pytest.skip("gcc not found")
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    names = sorted(set(re.findall(r"\b(pwlq_[a-z0-9_]+)\s*\(", open(os.path.join(root, "include", "pwlq.h")).read())))
+    text = "\n".join(re.sub(r"/\*.*?\*/", "", open(h).read(), flags=re.S) for h in HEADERS)
+    names = sorted(set(re.findall(r"\b(pwlq_[a-z0-9_]+)\s*\(", text)))
     assert len(names) > 20
     src = tmp_path / "use_header.c"
     body = "\n".join(f"    table[{i}] = (void (*)(void))&{n};" for i, n in enumerate(names))
-    src.write_text('#include "pwlq.h"\n'
+    src.write_text("".join(f'#include "{os.path.basename(h)}"\n' for h in HEADERS) +
                    f"void (*table[{len(names)}])(void);\n"
                    "void fill(void)\n{\n" + body + "\n}\n")
     r = subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-c",
