@@ -34,34 +34,61 @@ LANE_OPS_PER_EVAL = 9
 PEAK_LANE_OPS = 256 * 128 * 2.4e9
 
 
-def _measured_traffic(workload: int, kernel: str):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter runs
-    (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy), or None if this workload
-    was not measured."""
-    path = os.path.join(ROOT, "paper_2002_00104_amd", "measured_traffic.json")
-    try:
-        with open(path) as f:
-            m = json.load(f)
-        if m.get("workload") != workload:
-            return None
-        k = m["kernels"][kernel]
-        return k["read_bytes"] + k["written_bytes"]
-    except (OSError, KeyError, ValueError):
-        return None
+# One evaluation as this build's search kernel does it once the tile is partitioned by
+# candidate block: multiply (or fused multiply-add in the tail), round, subtract,
+# fused multiply-accumulate.
+LANE_OPS_PER_EVAL_PARTITIONED = 4
+PEAK_FLOPS_FP32 = 157.3e12          # the spec-sheet figure: packed fused multiply-adds
 
 
-def _measured_valu(workload: int, kernel: str):
-    """VALU wavefront-instructions per launch of `kernel` from the committed
-    rocprofv3 counter run (SQ_INSTS_VALU), or None if this workload was not measured."""
-    path = os.path.join(ROOT, "paper_2002_00104_amd", "measured_traffic.json")
+def sources_sha16() -> str:
+    """Fingerprint of the kernel sources a counter summary under profiles/ belongs to."""
+    import hashlib
+    d = os.path.join(ROOT, "paper_2002_00104_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".h", ".hip")):
+            with open(os.path.join(d, name), "rb") as f:
+                h.update(name.encode() + b"\0" + f.read() + b"\0")
+    return h.hexdigest()[:16]
+
+
+def _profile_record(name: str):
+    """The machine-readable line ('#json {...}') of a committed rocprofv3 summary
+    under profiles/, or None."""
+    path = os.path.join(ROOT, "profiles", name)
     try:
         with open(path) as f:
-            m = json.load(f)
-        if m.get("workload") != workload:
-            return None
-        return float(m["kernels"][kernel]["valu_wave_instructions"])
-    except (OSError, KeyError, ValueError):
-        return None
+            for line in f:
+                if line.startswith("#json "):
+                    return json.loads(line[6:])
+    except (OSError, ValueError):
+        pass
+    return None
+
+
+def _static_counters(tag: str, kernel: str):
+    """Counters of `kernel` from the committed counter runs of the workload `tag`
+    ('workload2', 'workload3_only_k9', ...): (valu wave-instructions per launch,
+    HBM bytes per launch, dict describing where they come from)."""
+    valu = traffic = None
+    src = {}
+    rec = _profile_record(f"valu_lds_counters_{tag}.txt")
+    if rec and kernel in rec.get("kernels", {}):
+        valu = float(rec["kernels"][kernel]["SQ_INSTS_VALU"])
+        src["executed"] = {"file": f"profiles/valu_lds_counters_{tag}.txt", "static": True,
+                           "counter": "SQ_INSTS_VALU per launch",
+                           "kernel_sources_sha16": rec.get("kernel_sources_sha16"),
+                           "matches_this_build": rec.get("kernel_sources_sha16") == sources_sha16()}
+    rec = _profile_record(f"hbm_traffic_{tag}.txt")
+    if rec and kernel in rec.get("kernels", {}):
+        k = rec["kernels"][kernel]
+        traffic = float(k["read_bytes"]) + float(k["written_bytes"])
+        src["traffic"] = {"file": f"profiles/hbm_traffic_{tag}.txt", "static": True,
+                          "counter": "FETCH_SIZE + WRITE_SIZE per launch, scaled by a plain copy",
+                          "kernel_sources_sha16": rec.get("kernel_sources_sha16"),
+                          "matches_this_build": rec.get("kernel_sources_sha16") == sources_sha16()}
+    return valu, traffic, src
 
 
 def main() -> int:
@@ -74,8 +101,11 @@ def main() -> int:
     ap.add_argument("--no-linear", action="store_true",
                     help="skip the timing of the integer inner-product kernel")
     ap.add_argument("--hot-path-only", action="store_true",
-                    help="time only the step (search_list + quantize_list): no packed output, "
-                         "fast search, analytic selectors or inner product")
+                    help="time only the step (search_list + quantize_list), eager and replayed "
+                         "from a HIP graph: no packed output, fast search, analytic selectors "
+                         "or inner product")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="skip the replay of the step from a HIP graph")
     ap.add_argument("--only-k", type=int, default=0,
                     help="keep only the tensors whose rows have this many elements "
                          "(e.g. 9: the depthwise channels of workload 3)")
@@ -158,9 +188,22 @@ def main() -> int:
     n_elements = sum(t.size for t in host)
     evals = n_elements * wl.n_cand
     value = evals / (ms_per_step * 1e-3)
+    keep_search = {k: v.clone() for k, v in out.items()}      # compared with the oracle below
     ks = float(np.mean(k_search_ms))
-    achieved = LANE_OPS_PER_EVAL * evals / (ks * 1e-3)
     emit_ms = float(np.mean(k_emit_ms))
+    tag = f"workload{wl.index}" + (f"_only_k{args.only_k}" if args.only_k else "")
+    valu, traffic, static_src = _static_counters(tag, pwlq.kernel_name(0))
+    fresh = valu is not None and static_src["executed"]["matches_this_build"]
+    # Lane-instructions of the dominant kernel per launch.  Executed: SQ_INSTS_VALU x 64 of the
+    # committed counter run of this workload, used only while the kernel sources are the
+    # ones that run was made with.  Otherwise the algorithmic count of the partitioned
+    # evaluation (4 per pair), which the executed count can only exceed.
+    lane_ops = valu * 64 if fresh else float(LANE_OPS_PER_EVAL_PARTITIONED) * evals
+    achieved = lane_ops / (ks * 1e-3)
+    # what the search kernel must move: the partitioned tile and its offsets in, one
+    # binary32 sum per (tile, candidate) out
+    shape = pwlq.last_search_shape()
+    algorithmic_bytes = 4.0 * n_elements + 4.0 * shape["tiles"] * (wl.n_cand + (wl.n_cand + 63) // 64 + 1)
     result = {
         "metric": "breakpoint-search candidate-elem evals/s; ResNet-50-shape per-channel PWLQ ms",
         "value": value,
@@ -190,9 +233,27 @@ def main() -> int:
             "bound": "alu",
             "achieved": achieved / 1e12,
             "peak": PEAK_LANE_OPS / 1e12,
-            "unit": "Tlane-op/s (fp32 VALU lane-instructions; 9 per evaluation, algorithmic)",
+            "unit": "Tlane-op/s (fp32 VALU instructions x active lanes; peak = 256 CUs x 128 "
+                    "lanes x 2.4 GHz, i.e. 157.3 TFLOP/s at 2 flop per lane-instruction)",
             "frac": achieved / PEAK_LANE_OPS,
-            "traffic": None if args.only_k else _measured_traffic(wl.index, pwlq.kernel_name(0)),
+            "lane_ops_counted": ("executed (static SQ_INSTS_VALU of the committed counter run, "
+                                 "live kernel time)" if fresh else
+                                 "algorithmic, 4 per evaluation (no counter run of this workload "
+                                 "for these kernel sources)"),
+            "lane_ops_per_eval": lane_ops / evals,
+            "algorithmic_frac": LANE_OPS_PER_EVAL_PARTITIONED * evals / (ks * 1e-3) / PEAK_LANE_OPS,
+            "canonical_equivalent": LANE_OPS_PER_EVAL * evals / (ks * 1e-3) / PEAK_LANE_OPS,
+            "canonical_equivalent_note": "9 lane-instructions per evaluation (the branch-free form "
+                                         "without the partition) over the same time and peak: a "
+                                         "speed-up over that form, not a utilisation; may exceed 1",
+            "flop_frac_of_157.3_TFLOPs": (lane_ops + evals) / (ks * 1e-3) / PEAK_FLOPS_FP32,
+            "flop_frac_note": "flops = lane-instructions + one per evaluation (the accumulate is a "
+                              "fused multiply-add); the 157.3 TFLOP/s figure needs packed fused "
+                              "multiply-adds, which this build does not use",
+            "traffic": traffic,
+            "algorithmic_bytes": algorithmic_bytes,
+            "static_sources": static_src,
+            "kernel_sources_sha16": sources_sha16(),
             "kernel_ms": ks,
             "kernel_evals_per_s": evals / (ks * 1e-3),
         },
@@ -206,14 +267,6 @@ def main() -> int:
             "kernel_ms": emit_ms,
         },
     }
-
-    # Instructions the kernel really issues (it needs fewer than the plain form's 9
-    # per evaluation, hence frac > 1 above): executed lane-instructions per second
-    # against the same peak.
-    valu = None if args.only_k else _measured_valu(wl.index, pwlq.kernel_name(0))
-    if valu is not None:
-        result["roofline"]["executed_lane_ops_per_eval"] = valu * 64 / evals
-        result["roofline"]["executed_frac"] = valu * 64 / (ks * 1e-3) / PEAK_LANE_OPS
 
     # What a plain device-to-device copy reaches on this chip (read + write bytes
     # per second), as the practical ceiling beside the 8 TB/s peak.
@@ -323,32 +376,6 @@ def main() -> int:
                     (mse_out[ok] * tl.group_counts(ok)).sum() / (best[ok] * tl.group_counts(ok)).sum()),
             }
 
-        # The same step recorded once into a HIP graph and replayed (the calls only
-        # launch kernels): what is left of the launch overhead, which is most of the
-        # time of the one-tensor workload.
-        keep = {k: v.clone() for k, v in out.items()}
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            step()
-        for _ in range(3):
-            graph.replay()
-        torch.cuda.synchronize()
-        nrep = max(20, min(200, int(200.0 / max(ms_per_step, 1e-3))))
-        g0 = time.perf_counter()
-        for _ in range(nrep):
-            graph.replay()
-        torch.cuda.synchronize()
-        g1 = time.perf_counter()
-        result["graph_replay"] = {
-            "ms_per_step": (g1 - g0) * 1e3 / nrep,
-            "eager_ms_per_step": ms_per_step,
-            "replays": nrep,
-            "same_outputs_as_eager": bool(all(torch.equal(keep[k], out[k], ) or
-                                              bool(torch.equal(torch.nan_to_num(keep[k].double()),
-                                                               torch.nan_to_num(out[k].double())))
-                                              for k in keep)),
-        }
-
         # Consumer of the packed format (Section 4): int8 activations [4096, 4096]
         # times a PWLQ-quantized [4096, 4096] linear weight (b = 4, Laplacian values of
         # workload 5's kind), three integer accumulators per output on the int8 matrix
@@ -388,9 +415,43 @@ def main() -> int:
                 "peak": 5000.0,
                 "unit": "TOP/s int8 (dense MFMA)",
                 "frac": 3.0 * ops / (lm * 1e-3) / 5e15,
+                "algorithmic_frac": ops / (lm * 1e-3) / 5e15,
+                "note": "frac counts the three matrix products the scheme needs per weight "
+                        "(centre codes, tail codes, tail signs); algorithmic_frac counts one "
+                        "multiply-add per (row, channel, k)",
                 "weight_bytes_per_element": (bl + 1) / 8.0,
             }
 
+    def graph_leg():
+        # The same step recorded once into a HIP graph and replayed (the calls only
+        # launch kernels): what is left of the launch overhead, which is most of the
+        # time of the one-tensor workload.
+        keep = {k: v.clone() for k, v in out.items()}
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        nrep = max(20, min(200, int(200.0 / max(ms_per_step, 1e-3))))
+        g0 = time.perf_counter()
+        for _ in range(nrep):
+            graph.replay()
+        torch.cuda.synchronize()
+        g1 = time.perf_counter()
+        result["graph_replay"] = {
+            "ms_per_step": (g1 - g0) * 1e3 / nrep,
+            "eager_ms_per_step": ms_per_step,
+            "replays": nrep,
+            "same_outputs_as_eager": bool(all(torch.equal(keep[k], out[k], ) or
+                                              bool(torch.equal(torch.nan_to_num(keep[k].double()),
+                                                               torch.nan_to_num(out[k].double())))
+                                              for k in keep)),
+        }
+
+
+    if not args.no_graph:
+        graph_leg()
     if not args.hot_path_only:
         extras()
 
@@ -409,17 +470,36 @@ def main() -> int:
             what = "the smaller half of the tensors"
         c0 = time.perf_counter()
         n_eval_cpu = 0
+        ref_k, ref_mse = [], []
         for t in sample:
             t = np.ascontiguousarray(t)
-            pwlq_ref.search(t, wl.bits, wl.n_cand, wl.mode)
+            r = pwlq_ref.search(t, wl.bits, wl.n_cand, wl.mode)
+            ref_k.append(r["k_star"])
+            ref_mse.append(r["mse"])
             n_eval_cpu += t.size * wl.n_cand
         c1 = time.perf_counter()
+        # the same groups from the timed GPU steps, side by side with the oracle's (the
+        # parity tests hold the tolerances; this only reports what the two runs gave)
+        gk, gm = keep_search["k_star"].cpu().numpy(), keep_search["mse"].cpu().numpy()
+        if wl.mode == synth.PER_CHANNEL:
+            pick = np.concatenate([tl.group_offsets[i] + np.arange(0, host[i].shape[0], stride)
+                                   for i in range(len(host))])
+        else:
+            pick = np.array([tl.group_offsets[int(i)] for i in order[: len(order) // 2]])
+        rk, rm = np.concatenate(ref_k), np.concatenate(ref_mse)
+        fin = rk > 0
         result["cpu_baseline"] = {
             "value": n_eval_cpu / (c1 - c0),
             "unit": "candidate-element evaluations/s",
             "cores": pwlq_ref.num_threads(),
             "kind": "oracle",
             "sample": f"search only, {what} ({n_eval_cpu:.3e} evaluations, {c1 - c0:.1f} s)",
+            "agreement_with_gpu": {
+                "groups": int(rk.size),
+                "k_star_equal": int((gk[pick] == rk).sum()),
+                "max_mse_rel_diff": float(np.max(np.abs(gm[pick][fin] - rm[fin]) /
+                                                 np.where(rm[fin] > 0, rm[fin], 1.0), initial=0.0)),
+            },
         }
     print(json.dumps(result), flush=True)
     return 0
