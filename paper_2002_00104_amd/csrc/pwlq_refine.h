@@ -158,7 +158,17 @@ __device__ inline void exact_tile(const float *__restrict__ src, int len,
                 for (int e = 0; e < kEpt; ++e)
                     if (tid + e * kT < len) acc0 += exact_error_sq(q0, a[e]);
             } else {
-                for (int i = tid; i < len; i += kT) acc0 += exact_error_sq(q0, fabsf(src[i]));
+                // four loads in flight per thread: the pass is bound by their latency
+                int i = tid;
+                for (; i + 3 * kT < len; i += 4 * kT) {
+                    const float a0 = fabsf(src[i]), a1 = fabsf(src[i + kT]),
+                                a2 = fabsf(src[i + 2 * kT]), a3 = fabsf(src[i + 3 * kT]);
+                    acc0 += exact_error_sq(q0, a0);
+                    acc0 += exact_error_sq(q0, a1);
+                    acc0 += exact_error_sq(q0, a2);
+                    acc0 += exact_error_sq(q0, a3);
+                }
+                for (; i < len; i += kT) acc0 += exact_error_sq(q0, fabsf(src[i]));
             }
         } else {
             const Pieces q1 = make_pieces(m, grid_point(m, k1, n), bits);
@@ -171,7 +181,20 @@ __device__ inline void exact_tile(const float *__restrict__ src, int len,
                     }
                 }
             } else {
-                for (int i = tid; i < len; i += kT) {
+                int i = tid;
+                for (; i + 3 * kT < len; i += 4 * kT) {
+                    const float a0 = fabsf(src[i]), a1 = fabsf(src[i + kT]),
+                                a2 = fabsf(src[i + 2 * kT]), a3 = fabsf(src[i + 3 * kT]);
+                    acc0 += exact_error_sq(q0, a0);
+                    acc1 += exact_error_sq(q1, a0);
+                    acc0 += exact_error_sq(q0, a1);
+                    acc1 += exact_error_sq(q1, a1);
+                    acc0 += exact_error_sq(q0, a2);
+                    acc1 += exact_error_sq(q1, a2);
+                    acc0 += exact_error_sq(q0, a3);
+                    acc1 += exact_error_sq(q1, a3);
+                }
+                for (; i < len; i += kT) {
                     const float av = fabsf(src[i]);
                     acc0 += exact_error_sq(q0, av);
                     acc1 += exact_error_sq(q1, av);
