@@ -17,14 +17,15 @@ extern "C" {
  * benchmarks: number of tiles, groups and work units.  Any pointer may be NULL. */
 void pwlq_last_search_shape(int64_t *n_tiles, int64_t *n_groups, int64_t *n_units);
 
-/* Benchmark aid.  With profiling enabled every search / quantize call records
- * HIP events on its own stream right before and after its dominant kernel
- * (role 0: the candidate-evaluation kernel of a search; role 1: the quantize
- * kernel; role 2: the prefix-sum evaluation kernel of a fast search; role 3: the
- * integer inner-product kernel).  pwlq_profile_last_ms waits for the later event of the most recent
- * call and returns the kernel's duration in milliseconds, or -1 if none was
- * recorded.  Process-wide, not thread-safe; off by default. */
-void pwlq_profile_enable(int on);
+/* Benchmark aid.  `roles` is a bit mask (0: off, the default).  With bit r set,
+ * every call that launches the kernel of role r records HIP events on its own
+ * stream right before and after that kernel (role 0: the candidate-evaluation
+ * kernel of a search; role 1: the quantize kernel; role 2: the prefix-sum
+ * evaluation kernel of a fast search; role 3: the integer inner-product
+ * kernel).  pwlq_profile_last_ms waits for the later event of the most recent
+ * launch of a role and returns the kernel's duration in milliseconds, or -1 if
+ * none was recorded.  Process-wide, not thread-safe. */
+void pwlq_profile_enable(int roles);
 double pwlq_profile_last_ms(int role);
 /* The same for an earlier launch of that role: back = 0 is the most recent one,
  * back = 1 the one before, up to the last 64 recorded launches; -1 beyond. */

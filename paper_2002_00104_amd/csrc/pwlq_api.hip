@@ -257,6 +257,27 @@ int upload_tables(const Plan &pl, char *ws, hipStream_t stream, Tables &tb)
     return PWLQ_OK;
 }
 
+// The quantize kernels' view of a small tensor table, for the kernel arguments.
+bool fill_emit_args(const Plan &pl, EmitArgs &ea)
+{
+    memset(&ea, 0, sizeof(ea));
+    if (pl.nt < 2 || pl.nt > kEmitArgTensors) return false;
+    for (int i = 0; i < pl.nt; ++i) {
+        const TensorRec &r = pl.recs[i];
+        ea.w[i] = (long long)reinterpret_cast<uintptr_t>(r.w);
+        ea.gcount[i] = r.gcount;
+        ea.out_elem[i] = r.out_elem;
+        ea.out_group[i] = r.out_group;
+        ea.out_code_byte[i] = r.out_code_byte;
+        ea.out_flag_byte[i] = r.out_flag_byte;
+        ea.ngroups[i] = r.ngroups;
+        ea.emit_prefix[i] = pl.emit_prefix[i];
+    }
+    ea.emit_prefix[pl.nt] = pl.emit_prefix[pl.nt];
+    ea.nt = pl.nt;
+    return true;
+}
+
 int launch_status(const char *what)
 {
     hipError_t e = hipGetLastError();
@@ -268,7 +289,7 @@ int launch_status(const char *what)
 // A ring of the last kProfRing recorded launches per role, so that a benchmark
 // can time a run of calls without waiting inside it.
 constexpr int kProfRoles = 4, kProfRing = 64;
-bool g_profile = false;
+unsigned g_profile = 0;         // bit r: events are recorded around the kernel of role r
 hipEvent_t g_ev[kProfRoles][kProfRing][2];
 bool g_ev_made = false;
 long long g_ev_count[kProfRoles] = {0, 0, 0, 0};     // launches recorded so far
@@ -276,7 +297,7 @@ long long g_ev_count[kProfRoles] = {0, 0, 0, 0};     // launches recorded so far
 // idx = 2*role for the event before the kernel, 2*role+1 for the one after it
 void profile_mark(int idx, hipStream_t stream)
 {
-    if (!g_profile) return;
+    if (!((g_profile >> (idx >> 1)) & 1u)) return;
     if (!g_ev_made) {
         for (auto &role : g_ev)
             for (auto &slot : role)
@@ -481,10 +502,17 @@ int run_quantize(const pwlq_tensor_desc *desc, int n_tensors, int bits, int mode
     }
     hipStream_t stream = (hipStream_t)stream_v;
     Tables tb;
-    rc = upload_tables(pl, (char *)workspace, stream, tb);
-    if (rc) return rc;
+    static_assert(sizeof(Tables) + sizeof(EmitArgs) + 64 <= 4096, "a launch passes at most 4 KB");
+    EmitArgs ea;
+    if (fill_emit_args(pl, ea)) {          // the table travels with the launch
+        memset(&tb, 0, sizeof(tb));
+        tb.nt = pl.nt;
+    } else {
+        rc = upload_tables(pl, (char *)workspace, stream, tb);
+        if (rc) return rc;
+    }
     profile_mark(2, stream);
-    k_emit<<<(int)pl.n_chunks, kWG, 0, stream>>>(tb, bits, p_star, m, codes, flags, w_hat);
+    k_emit<<<(int)pl.n_chunks, kWG, 0, stream>>>(tb, ea, bits, p_star, m, codes, flags, w_hat);
     profile_mark(3, stream);
     return launch_status("quantize launch");
 }
@@ -510,9 +538,15 @@ int run_quantize_packed(const pwlq_tensor_desc *desc, int n_tensors, int bits, i
     }
     hipStream_t stream = (hipStream_t)stream_v;
     Tables tb;
-    rc = upload_tables(pl, (char *)workspace, stream, tb);
-    if (rc) return rc;
-    k_emit_packed<<<(int)pl.n_chunks, kWG, 0, stream>>>(tb, bits, p_star, m, packed_codes,
+    EmitArgs ea;
+    if (fill_emit_args(pl, ea)) {
+        memset(&tb, 0, sizeof(tb));
+        tb.nt = pl.nt;
+    } else {
+        rc = upload_tables(pl, (char *)workspace, stream, tb);
+        if (rc) return rc;
+    }
+    k_emit_packed<<<(int)pl.n_chunks, kWG, 0, stream>>>(tb, ea, bits, p_star, m, packed_codes,
                                                         packed_flags, w_hat);
     return launch_status("packed quantize launch");
 }
@@ -853,7 +887,7 @@ int pwlq_quantize_packed_list(const pwlq_tensor_desc *desc, int n_tensors, int b
 
 const char *pwlq_last_error(void) { return g_error; }
 
-void pwlq_profile_enable(int on) { g_profile = on != 0; }
+void pwlq_profile_enable(int roles) { g_profile = (unsigned)roles & ((1u << kProfRoles) - 1u); }
 
 double pwlq_profile_ms(int role, int back)
 {

@@ -33,12 +33,57 @@ __device__ inline Pieces group_pieces(const float *__restrict__ p_star,
     return make_pieces(m_in[og], p_star[og], bits);
 }
 
+// What the quantize kernels need to know of a tensor.  A model-level call of up
+// to kEmitArgTensors tensors carries these fields inside the kernel arguments
+// (EmitArgs), so that it launches nothing but the kernel itself; a longer table
+// is read from the workspace like every other kernel's.
+constexpr int kEmitArgTensors = 56;
+struct EmitArgs {
+    long long w[kEmitArgTensors];               // device address of the weights
+    long long gcount[kEmitArgTensors], out_elem[kEmitArgTensors], out_group[kEmitArgTensors];
+    long long out_code_byte[kEmitArgTensors], out_flag_byte[kEmitArgTensors];
+    int ngroups[kEmitArgTensors];
+    int emit_prefix[kEmitArgTensors + 1];       // first chunk of each tensor, then the total
+    int nt;                                     // 0: not used, the table is in the workspace
+};
+struct EmitRec {
+    const float *w;
+    long long gcount, out_elem, out_group, out_code_byte, out_flag_byte;
+    int ngroups, emit_base;
+};
+__device__ inline EmitRec emit_rec(const Tables &tb, const EmitArgs &ea, int chunk)
+{
+    EmitRec e;
+    if (ea.nt > 0) {
+        const int i = find_tensor(ea.emit_prefix, ea.nt, chunk);
+        e.w = reinterpret_cast<const float *>(uni(ea.w[i]));
+        e.gcount = uni(ea.gcount[i]);
+        e.out_elem = uni(ea.out_elem[i]);
+        e.out_group = uni(ea.out_group[i]);
+        e.out_code_byte = uni(ea.out_code_byte[i]);
+        e.out_flag_byte = uni(ea.out_flag_byte[i]);
+        e.ngroups = uni(ea.ngroups[i]);
+        e.emit_base = uni(ea.emit_prefix[i]);
+    } else {
+        const TensorRec r = rec_of(tb, find_tensor(tb.emit_prefix, tb.nt, chunk));
+        e.w = r.w;
+        e.gcount = r.gcount;
+        e.out_elem = r.out_elem;
+        e.out_group = r.out_group;
+        e.out_code_byte = r.out_code_byte;
+        e.out_flag_byte = r.out_flag_byte;
+        e.ngroups = r.ngroups;
+        e.emit_base = r.emit_base;
+    }
+    return e;
+}
+
 // A workgroup streams one chunk of kEmitChunk consecutive elements of one
 // tensor: 16 bytes in, 4 + 4 + 16 bytes out per lane and access, four accesses
 // in flight per thread.  The group of an element is its row-major index
 // divided by the group length; a vector of four that stays inside one group
 // shares one set of parameters.
-__global__ __launch_bounds__(kWG) void k_emit(Tables tb, int bits,
+__global__ __launch_bounds__(kWG) void k_emit(Tables tb, EmitArgs ea, int bits,
                                               const float *__restrict__ p_star,
                                               const float *__restrict__ m_in,
                                               uint8_t *__restrict__ codes,
@@ -46,8 +91,7 @@ __global__ __launch_bounds__(kWG) void k_emit(Tables tb, int bits,
                                               float *__restrict__ w_hat)
 {
     const int chunk = blockIdx.x;
-    const int tensor = find_tensor(tb.emit_prefix, tb.nt, chunk);
-    const TensorRec r = rec_of(tb, tensor);
+    const EmitRec r = emit_rec(tb, ea, chunk);
     const long long total = (long long)r.ngroups * r.gcount;
     const long long e0 = (long long)(chunk - r.emit_base) * kEmitChunk;
     const float *src = r.w;
@@ -125,7 +169,7 @@ __global__ __launch_bounds__(kWG) void k_emit(Tables tb, int bits,
 constexpr int kPackPass = 8 * kWG;      // elements per pass of a workgroup
 static_assert(kEmitChunk % kPackPass == 0 && kEmitChunk % (4 * kWG) == 0, "a chunk is a whole number of passes");
 
-__global__ __launch_bounds__(kWG) void k_emit_packed(Tables tb, int bits,
+__global__ __launch_bounds__(kWG) void k_emit_packed(Tables tb, EmitArgs ea, int bits,
                                                      const float *__restrict__ p_star,
                                                      const float *__restrict__ m_in,
                                                      uint8_t *__restrict__ packed_codes,
@@ -138,8 +182,7 @@ __global__ __launch_bounds__(kWG) void k_emit_packed(Tables tb, int bits,
     uint8_t *flag_bytes = reinterpret_cast<uint8_t *>(flag_stage);
     const int tid = threadIdx.x;
     const int chunk = blockIdx.x;
-    const int tensor = find_tensor(tb.emit_prefix, tb.nt, chunk);
-    const TensorRec r = rec_of(tb, tensor);
+    const EmitRec r = emit_rec(tb, ea, chunk);
     const long long total = (long long)r.ngroups * r.gcount;
     const float *src = r.w;
     uint8_t *co = packed_codes + r.out_code_byte;

@@ -444,8 +444,10 @@ def linear_i8(xq: torch.Tensor, s_x: float, z_x: float, packed_codes: torch.Tens
     return y, acc
 
 
-def profile_enable(on: bool) -> None:
-    lib.pwlq_profile_enable(1 if on else 0)
+def profile_enable(roles) -> None:
+    """roles: False / 0 = off, True = every role, else a bit mask (bit 0 search kernel,
+    bit 1 quantize kernel, bit 2 prefix-sum kernel, bit 3 inner-product kernel)."""
+    lib.pwlq_profile_enable(0xF if roles is True else int(roles))
 
 
 def profile_last_ms(role: int) -> float:
