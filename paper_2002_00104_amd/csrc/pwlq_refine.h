@@ -230,6 +230,7 @@ __device__ inline void exact_tile(const float *__restrict__ src, int len,
 
 constexpr int kListCap = 2048;   // kept candidates of a single-tile group, per round (256-thread workgroups)
 constexpr int kListCapSmall = 1024;   // ... of a one-wavefront workgroup
+template <int kT> struct RowRegs { static constexpr int value = kT == 64 ? 16 : 4; };   // 1024 candidates either way
 
 // The thread's elements are loaded first, so that their memory latency
 // overlaps the filtering that follows.
@@ -245,6 +246,21 @@ __device__ inline void exact_body(const TensorRec &r, const TileInfo &ti, int t,
     float a[kEpt > 0 ? kEpt : 1];
     load_tile<kEpt, kT>(ti.src, ti.len, a);
     const bool single = r.tpg == 1;
+    // Up to kRowRegs * kT candidates: a single-tile group's row of filter sums stays in
+    // registers between the two passes over it (minimum, then selection).  Its loads are
+    // issued here, together with the elements' and before anything waits for the group's
+    // absmax: the kernel is bound by the latency of its loads, not by their volume.
+    constexpr int kRowRegs = RowRegs<kT>::value;
+    const bool in_regs = n <= kRowRegs * kT;
+    const float *row = sse32 + (long long)t * n;
+    float rv[kRowRegs];
+    if (single && in_regs) {
+#pragma unroll
+        for (int x = 0; x < kRowRegs; ++x) {
+            const int k0 = tid + x * kT;
+            rv[x] = (k0 < n) ? row[k0] : __builtin_inff();
+        }
+    }
     const float m = gm[ti.group];
     const long long og = r.out_group + ti.group_local;
     const bool usable = (m > 0.0f) && (m < __builtin_inff());
@@ -268,9 +284,18 @@ __device__ inline void exact_body(const TensorRec &r, const TileInfo &ti, int t,
         __syncthreads();
         exact_tile<kEpt, kT>(ti.src, ti.len, a, m, n, bits, llist, 1, true, nullptr, lds, st);
     } else if (usable) {
-        const float *row = sse32 + (long long)t * n;
         float mnf = __builtin_inff();
-        for (int k0 = tid; k0 < n; k0 += kT) mnf = fminf(mnf, row[k0]);
+        if (in_regs) {
+#pragma unroll
+            for (int x = 0; x < kRowRegs; ++x) mnf = fminf(mnf, rv[x]);
+        } else {
+            int k0 = tid;
+            for (; k0 + 3 * kT < n; k0 += 4 * kT) {
+                const float v0 = row[k0], v1 = row[k0 + kT], v2 = row[k0 + 2 * kT], v3 = row[k0 + 3 * kT];
+                mnf = fminf(fminf(mnf, fminf(v0, v1)), fminf(v2, v3));
+            }
+            for (; k0 < n; k0 += kT) mnf = fminf(mnf, row[k0]);
+        }
         const double mn = block_min<kT / 64>((double)mnf, lds);
         const double thr = keep_threshold(mn, (double)r.gcount, n, r.fast != 0);
         // the sums are binary32: v <= thr exactly when v <= the largest binary32 value not above thr
@@ -281,8 +306,16 @@ __device__ inline void exact_body(const TensorRec &r, const TileInfo &ti, int t,
             if (tid == 0) *lcount = 0;
             __syncthreads();
             const int rend = (rbase + kCap < n) ? rbase + kCap : n;
-            for (int k0 = rbase + tid; k0 < rend; k0 += kT)
-                if (row[k0] <= thrf) llist[atomicAdd(lcount, 1)] = k0 + 1;
+            if (in_regs) {
+#pragma unroll
+                for (int x = 0; x < kRowRegs; ++x) {
+                    const int k0 = tid + x * kT;
+                    if (k0 >= rbase && k0 < rend && rv[x] <= thrf) llist[atomicAdd(lcount, 1)] = k0 + 1;
+                }
+            } else {
+                for (int k0 = rbase + tid; k0 < rend; k0 += kT)
+                    if (row[k0] <= thrf) llist[atomicAdd(lcount, 1)] = k0 + 1;
+            }
             __syncthreads();
             const int count = uni(*lcount);
             exact_tile<kEpt, kT>(ti.src, ti.len, a, m, n, bits, llist, count, true, nullptr, lds, st);
@@ -334,7 +367,7 @@ __global__ __launch_bounds__(kT) void k_exact(Tables tb, int tile_begin, int n, 
         if (ti.len <= kT) PWLQ_EXACT(1);
         else if (ti.len <= 4 * kT) PWLQ_EXACT(4);
         else if (ti.len <= 10 * kT) PWLQ_EXACT(10);
-        else PWLQ_EXACT(0);     // longer tiles are re-read per pass: holding them measured slower
+        else PWLQ_EXACT(0);     // longer tiles are re-read per pass: holding 16 per thread measured 15 % slower
     }
 #undef PWLQ_EXACT
 }
