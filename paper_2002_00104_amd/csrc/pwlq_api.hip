@@ -546,8 +546,25 @@ int run_quantize_packed(const pwlq_tensor_desc *desc, int n_tensors, int bits, i
         rc = upload_tables(pl, (char *)workspace, stream, tb);
         if (rc) return rc;
     }
-    k_emit_packed<<<(int)pl.n_chunks, kWG, 0, stream>>>(tb, ea, bits, p_star, m, packed_codes,
-                                                        packed_flags, w_hat);
+#define PWLQ_PACKED_CASE(B)                                                                        \
+    case B:                                                                                        \
+        if (w_hat)                                                                                 \
+            k_emit_packed<B, 8><<<(int)pl.n_chunks, kEmitChunk / 8, 0, stream>>>(                  \
+                tb, ea, p_star, m, packed_codes, packed_flags, w_hat);                             \
+        else                                                                                       \
+            k_emit_packed<B, 16><<<(int)pl.n_chunks, kEmitChunk / 16, 0, stream>>>(                \
+                tb, ea, p_star, m, packed_codes, packed_flags, w_hat);                             \
+        break;
+    switch (bits) {
+        PWLQ_PACKED_CASE(2)
+        PWLQ_PACKED_CASE(3)
+        PWLQ_PACKED_CASE(4)
+        PWLQ_PACKED_CASE(5)
+        PWLQ_PACKED_CASE(6)
+        PWLQ_PACKED_CASE(7)
+        PWLQ_PACKED_CASE(8)
+    }
+#undef PWLQ_PACKED_CASE
     return launch_status("packed quantize launch");
 }
 

@@ -278,6 +278,7 @@ __global__ __launch_bounds__(kFastWG) void k_fast(Tables tb, int tile_begin, int
 
     const bool usable = (m > 0.0f) && (m < __builtin_inff());
     const float nf = (float)n;
+    const float scale = usable ? nf / m : 0.0f;
     int shift = 16;                        // T = 2048: 128 buckets per octave
     for (int x = T; x < 2048; x <<= 1) ++shift;
     const int base = (__float_as_int(nf) >> shift) - (T - 1);
@@ -287,7 +288,7 @@ __global__ __launch_bounds__(kFastWG) void k_fast(Tables tb, int tile_begin, int
     for (int e = 0; e < kFastPer; ++e) {
         const int i = tid + e * kFastWG;
         if (i < len) {
-            const float u = usable ? to_units(a[e], m, nf) : 0.0f;
+            const float u = usable ? to_units(a[e], scale, nf) : 0.0f;
             a[e] = u;
             atomicAdd(&cnt[fast_bucket(u, shift, base)], 1);
         }

@@ -38,9 +38,11 @@ __global__ __launch_bounds__(kWG) void k_tile_absmax(Tables tb, float *__restric
 // breakpoint at u = k.  Bucket j holds the elements whose region differs among
 // the candidates 64j+1 .. 64j+64; every earlier bucket is centre for all of
 // them, every later bucket is tail for all of them.
-__device__ inline float to_units(float a, float m, float nf)
+// `scale` = n/m rounded once: two roundings per element, as many as (a/m)*n has,
+// and no division per element.
+__device__ inline float to_units(float a, float scale, float nf)
 {
-    float u = (a / m) * nf;
+    float u = a * scale;
     return fminf(fmaxf(u, 0.0f), nf);     // also maps a NaN to 0
 }
 // smallest candidate with u <= k, 0-based
@@ -131,6 +133,7 @@ __global__ __launch_bounds__(kT) void k_prep(Tables tb, int tile_begin, int n, i
 
     const bool usable = (m > 0.0f) && (m < __builtin_inff());
     const float nf = (float)n;
+    const float scale = usable ? nf / m : 0.0f;
     const int padded = (len + kVec - 1) / kVec * kVec;
     const int pad = padded - len;
     float *out = sorted + ti.sorted_off;
@@ -146,7 +149,7 @@ __global__ __launch_bounds__(kT) void k_prep(Tables tb, int tile_begin, int n, i
     for (int e = 0; e < kPer; ++e) {
         const int i = tid + e * kT;
         if (i < len) {
-            const float u = usable ? to_units(a[e], m, nf) : 0.0f;
+            const float u = usable ? to_units(a[e], scale, nf) : 0.0f;
             a[e] = u;
             const int b = kFine ? candidate_bin(u, n) : bucket_of(u);
             // fire-and-forget LDS add: the column is private, the atomic form only keeps

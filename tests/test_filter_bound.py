@@ -31,7 +31,7 @@ def half_slack(T, count, n, fast):
 def to_units(w, n):
     a = np.abs(w.astype(F32))
     m = a.max()
-    u = (a / m) * F32(n)                     # two binary32 roundings, as in the kernel
+    u = a * (F32(n) / m)                     # two binary32 roundings, as in the kernel
     return np.clip(u, F32(0), F32(n)), m
 
 
