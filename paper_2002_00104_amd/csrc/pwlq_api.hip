@@ -115,7 +115,13 @@ int build_plan(Plan &pl, const pwlq_tensor_desc *desc, int n_tensors, int n_cand
         long long total_tiles = 0;
         for (const TensorRec &r : tmp) total_tiles += r.ntiles;
         const int cap = (int)std::max(1LL, total_tiles / kMinUnits);
-        for (TensorRec &r : tmp) r.tpu = std::min(r.tpu, cap);
+        // tiles of at most kTinyTile elements cost a unit little each (no offsets, loads one
+        // tile ahead): up to kTinyUnit per unit while they still make about a thousand units
+        long long tiny_tiles = 0;
+        for (const TensorRec &r : tmp) if (r.tile_len <= kTinyTile && r.tpg == 1) tiny_tiles += r.ntiles;
+        const int tiny_cap = (int)std::min((long long)kTinyUnit, std::max((long long)cap, tiny_tiles / 1024));
+        for (TensorRec &r : tmp)
+            r.tpu = std::min(r.tpu, (r.tile_len <= kTinyTile && r.tpg == 1) ? tiny_cap : cap);
     }
     // longest tiles first: the search kernel's workgroups are dispatched in
     // index order, so the big items start early and the small ones fill gaps

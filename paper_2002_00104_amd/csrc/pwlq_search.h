@@ -82,6 +82,23 @@ __device__ inline float zone_mixed(const float *__restrict__ us, int begin, int 
     return outer;
 }
 
+// One vector of 8 elements in the per-lane form (see zone_mixed).
+__device__ inline void mixed8(const float8 &cur, float kf, float rc, float rt, float ct,
+                              float stepc, float stept, float &acc)
+{
+#pragma unroll
+    for (int e = 0; e < kVec; ++e) {
+        const float u = cur[e];
+        const bool tail = u > kf;
+        const float tc = u * rc;
+        const float tt = __builtin_fmaf(u, rt, ct);
+        const float t = tail ? tt : tc;
+        const float step = tail ? stept : stepc;
+        const float err = (t - __builtin_rintf(t)) * step;
+        acc = __builtin_fmaf(err, err, acc);
+    }
+}
+
 // The same bucket when the tile is ordered by ceil(u) and `sw` is the position at
 // which this lane's candidate switches from centre to tail.  A vector of 8
 // elements that lies on one side of the lane's switch is evaluated with the
@@ -188,6 +205,30 @@ __global__ __launch_bounds__(kSearchWaves * 64) void k_search(Tables tb, int n, 
     const float ct = -kf * rt;
     const float stepc = kf / Lf;
     const float stept = nk / Lf;
+
+    // Tiles of at most kTinyTile elements (depthwise 3x3 filters: 9) are two vectors.  A
+    // wavefront would spend its time waiting for the bucket offsets and then for the
+    // elements of tile after tile; instead every element is evaluated in the per-lane
+    // form (no offsets: the order inside the tile does not matter, the zero padding adds
+    // nothing), and the next tile's vectors are loaded while this one is evaluated.
+    if (r.tile_len <= kTinyTile && r.tpg == 1) {
+        const bool two = r.tile_len > kVec;                 // the second vector holds elements
+        const float *us = sorted + (r.sorted_base + (long long)(first - r.tile_base) * r.stride);
+        float8 c0 = load8(us), c1 = load8(us + kVec);       // the spare vector of a tile, if not its second
+        for (int t = first; t < last; ++t) {
+            // the tile after the tensor's last one does not exist: read this one again
+            const float *nx = (t + 1 < last) ? us + r.stride : us;
+            const float8 n0 = load8(nx), n1 = load8(nx + kVec);
+            float acc0 = 0.0f, acc1 = 0.0f;
+            mixed8(c0, kf, rc, rt, ct, stepc, stept, acc0);
+            if (two) mixed8(c1, kf, rc, rt, ct, stepc, stept, acc1);
+            if (live) sse32[(long long)t * n + (k - 1)] = acc0 + acc1;
+            c0 = n0;
+            c1 = n1;
+            us = nx;
+        }
+        return;
+    }
 
     for (int t = first; t < last; ++t) {
         const int local = t - r.tile_base;
