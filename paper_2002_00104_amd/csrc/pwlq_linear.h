@@ -130,7 +130,7 @@ __device__ inline void planes4(uint32_t codes, uint32_t f, int bits, uint32_t &w
     const uint32_t smask = (0x80808080u - sgn) ^ 0x80808080u;          // negative codes
     const uint32_t neg = (0x80808080u - mag) ^ 0x80808080u;            // -mag per byte (mag <= 127)
     const uint32_t val = (neg & smask) | (mag & ~smask);
-    const uint32_t f01 = ((f & 0xfu) * 0x00204081u) & 0x01010101u;     // region bit of each byte
+    const uint32_t f01 = __umul24(f & 0xfu, 0x00204081u) & 0x01010101u;   // region bit of each byte (24-bit multiply: full rate)
     const uint32_t fm = (0x80808080u - f01) ^ 0x80808080u;             // tail bytes
     w1 = val & ~fm;
     w2 = val & fm;
