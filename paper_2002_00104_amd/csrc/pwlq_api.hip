@@ -446,9 +446,14 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
         // positions written out: worth it only where buckets can be long), short
         // ones by block of 64 candidates
         if (pl.fine) {
-            if (large)      // 512 threads x 16 elements: 256 x 32 measured 7-27 % slower, 1024 x 8 slower still
-                k_prep<false, true, 512, 16><<<nt_large, 512, sizeof(int) * n_cand + stage_bytes(longest), stream>>>(
-                    tb, 0, n_cand, pl.nblk, tile_max, gm, offsets, fine, sorted);
+            if (large) {    // 512 threads x 16 elements: 256 x 32 measured 7-27 % slower, 1024 x 8 slower still
+                if (longest <= 256 * 16)    // tiles of at most 4096 elements: smaller workgroups, twice as many in flight
+                    k_prep<false, true, 256, 16><<<nt_large, 256, sizeof(int) * n_cand + stage_bytes(longest), stream>>>(
+                        tb, 0, n_cand, pl.nblk, tile_max, gm, offsets, fine, sorted);
+                else
+                    k_prep<false, true, 512, 16><<<nt_large, 512, sizeof(int) * n_cand + stage_bytes(longest), stream>>>(
+                        tb, 0, n_cand, pl.nblk, tile_max, gm, offsets, fine, sorted);
+            }
             if (small)
                 k_prep<true, false, 64, kSmallPer><<<nt_small, 64, sizeof(int) * nb2 * 64 + stage_bytes(longest_small), stream>>>(
                     tb, nt_large, n_cand, pl.nblk, tile_max, gm, offsets, fine, sorted);

@@ -145,6 +145,9 @@ __global__ __launch_bounds__(kT) void k_prep(Tables tb, int tile_begin, int n, i
     // the counts nor their prefix sums carry into the other half)
     const int nb2 = (nblk + 1) >> 1;
     if (kPrivate) for (int w = 0; w < nb2; ++w) hist[w * kT + tid] = 0;
+    // shared counters: the value the add returns is the element's rank inside its bin (in
+    // arrival order), kept for pass B, which then needs no second round of atomics
+    int rank[kPrivate ? 1 : kPer];
 #pragma unroll
     for (int e = 0; e < kPer; ++e) {
         const int i = tid + e * kT;
@@ -152,10 +155,10 @@ __global__ __launch_bounds__(kT) void k_prep(Tables tb, int tile_begin, int n, i
             const float u = usable ? to_units(a[e], scale, nf) : 0.0f;
             a[e] = u;
             const int b = kFine ? candidate_bin(u, n) : bucket_of(u);
-            // fire-and-forget LDS add: the column is private, the atomic form only keeps
-            // the updates pipelined instead of read-modify-write round trips
+            // private column: fire-and-forget LDS add; the atomic form only keeps the
+            // updates pipelined instead of read-modify-write round trips
             if (kPrivate) atomicAdd(&hist[(b >> 1) * kT + tid], 1 << (16 * (b & 1)));
-            else atomicAdd(&hist[b], 1);
+            else rank[e] = atomicAdd(&hist[b], 1);
         }
     }
 
@@ -237,7 +240,7 @@ __global__ __launch_bounds__(kT) void k_prep(Tables tb, int tile_begin, int n, i
                 pos = wtot[b * kW + wave] + ((old >> sh) & 0xffff);
             }
             else {
-                pos = atomicAdd(&hist[b], 1);
+                pos = hist[b] + rank[e];          // hist now holds the first position of each bin
             }
             stage[pad + pos] = u;
         }
