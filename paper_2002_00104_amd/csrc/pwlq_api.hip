@@ -303,13 +303,7 @@ long long g_ev_count[kProfRoles] = {0, 0, 0, 0};     // launches recorded so far
 // idx = 2*role for the event before the kernel, 2*role+1 for the one after it
 void profile_mark(int idx, hipStream_t stream)
 {
-    if (!((g_profile >> (idx >> 1)) & 1u)) return;
-    if (!g_ev_made) {
-        for (auto &role : g_ev)
-            for (auto &slot : role)
-                for (auto &ev : slot) (void)hipEventCreate(&ev);
-        g_ev_made = true;
-    }
+    if (!((g_profile >> (idx >> 1)) & 1u) || !g_ev_made) return;
     const int role = idx >> 1;
     (void)hipEventRecord(g_ev[role][g_ev_count[role] % kProfRing][idx & 1], stream);
     if (idx & 1) ++g_ev_count[role];
@@ -481,9 +475,17 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
         k_group_sum<<<(unsigned)group_sum_wgs, kWG, 0, stream>>>(tb, n_cand, sse32, gsum);
         k_flag<<<(int)pl.n_mgroups, kWG, 0, stream>>>(tb, n_cand, gm, gsum, klist);
     }
-    if (nt_large > 0)
-        k_exact<kWG><<<nt_large, kWG, 0, stream>>>(tb, 0, n_cand, bits, gm, sse32, klist, part64, p_star,
-                                                   m_out, k_star, mse);
+    if (nt_large > 0) {
+        // single-tile groups only: workgroups of two wavefronts, twice as many in flight (the
+        // stage is bound by latency); with groups spread over tiles, where a tile's threads
+        // share the evaluation of the group's whole list, four wavefronts measured faster
+        if (pl.n_mgroups == 0)
+            k_exact<128><<<nt_large, 128, 0, stream>>>(tb, 0, n_cand, bits, gm, sse32, klist, part64, p_star,
+                                                       m_out, k_star, mse);
+        else
+            k_exact<kWG><<<nt_large, kWG, 0, stream>>>(tb, 0, n_cand, bits, gm, sse32, klist, part64, p_star,
+                                                       m_out, k_star, mse);
+    }
     if (nt_small > 0)
         k_exact<64><<<nt_small, 64, 0, stream>>>(tb, nt_large, n_cand, bits, gm, sse32, klist, part64,
                                                  p_star, m_out, k_star, mse);
@@ -915,7 +917,18 @@ int pwlq_quantize_packed_list(const pwlq_tensor_desc *desc, int n_tensors, int b
 
 const char *pwlq_last_error(void) { return g_error; }
 
-void pwlq_profile_enable(int roles) { g_profile = (unsigned)roles & ((1u << kProfRoles) - 1u); }
+void pwlq_profile_enable(int roles)
+{
+    // the events are made here, on the first call that enables anything, so that no
+    // call that launches kernels pays for them
+    if (roles && !g_ev_made) {
+        for (auto &role : g_ev)
+            for (auto &slot : role)
+                for (auto &ev : slot) (void)hipEventCreate(&ev);
+        g_ev_made = true;
+    }
+    g_profile = (unsigned)roles & ((1u << kProfRoles) - 1u);
+}
 
 double pwlq_profile_ms(int role, int back)
 {

@@ -230,7 +230,7 @@ __device__ inline void exact_tile(const float *__restrict__ src, int len,
 
 constexpr int kListCap = 2048;   // kept candidates of a single-tile group, per round (256-thread workgroups)
 constexpr int kListCapSmall = 1024;   // ... of a one-wavefront workgroup
-template <int kT> struct RowRegs { static constexpr int value = kT == 64 ? 16 : 4; };   // 1024 candidates either way
+template <int kT> struct RowRegs { static constexpr int value = 1024 / kT; };   // 1024 candidates either way
 
 // The thread's elements are loaded first, so that their memory latency
 // overlaps the filtering that follows.
