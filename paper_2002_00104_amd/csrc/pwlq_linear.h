@@ -230,6 +230,50 @@ __device__ inline void lin_load(LinStage<kBits> &st, const int8_t *__restrict__ 
     st.flags = *reinterpret_cast<const uint16_t *>(pflags + (e0 >> 3));
 }
 
+// The same loads for a step that lies wholly below K, from addresses split into
+// a base that is the same in every lane and changes from step to step (scalar
+// arithmetic) and a 32-bit offset per thread that never changes (computed once,
+// before the loop): no vector address arithmetic per step.
+template <int kBits>
+struct LinOffsets {
+    unsigned a[kLinAVec];      // from xq + row0*K + k0
+    unsigned codes, flags;     // from the streams at element col0*K + k0
+};
+
+template <int kBits>
+__device__ inline LinOffsets<kBits> lin_offsets(long long M, long long K, long long N,
+                                                long long row0, long long col0)
+{
+    LinOffsets<kBits> o;
+    const int t = threadIdx.x;
+#pragma unroll
+    for (int v = 0; v < kLinAVec; ++v) {
+        const int piece = t + v * kLinWG;
+        long long r = row0 + (piece >> 2);
+        r = r < M ? r : M - 1;
+        o.a[v] = (unsigned)((r - row0) * K) + (unsigned)((t & 3) * 16);     // < 192 * 2^22 + 64
+    }
+    long long n = col0 + (t >> 2);
+    n = n < N ? n : N - 1;
+    const unsigned piece16 = (unsigned)((n - col0) * (K >> 4)) + (unsigned)(t & 3);   // in runs of 16 elements
+    o.codes = piece16 * (2 * kBits);
+    o.flags = piece16 * 2;
+    return o;
+}
+
+template <int kBits>
+__device__ inline void lin_load_whole(LinStage<kBits> &st, const LinOffsets<kBits> &o,
+                                      const int8_t *__restrict__ a_base,
+                                      const uint8_t *__restrict__ code_base,
+                                      const uint8_t *__restrict__ flag_base)
+{
+#pragma unroll
+    for (int v = 0; v < kLinAVec; ++v)
+        st.a[v] = *reinterpret_cast<const v4i *>(a_base + o.a[v]);
+    load_raw16<kBits>(code_base + o.codes, 0, st.codes);
+    st.flags = *reinterpret_cast<const uint16_t *>(flag_base + o.flags);
+}
+
 // Writes one step into LDS: activations as they are, weights decoded into the
 // three planes.
 template <int kBits>
@@ -307,7 +351,7 @@ __device__ inline void lin_step(v16i (&acc)[kLinMT][3], const LinStage<kBits> &n
 // step kt are read from LDS buffer kt&1, step kt+1 (loaded one step ago) is
 // decoded into the other buffer, the matrix cores run, one barrier.
 template <int kBits>
-__global__ __launch_bounds__(kLinWG) void k_linear(const int8_t *__restrict__ xq, long long M,
+__global__ __launch_bounds__(kLinWG, 2) void k_linear(const int8_t *__restrict__ xq, long long M,
                                                    long long K, float s_x, float z_x,
                                                    const uint8_t *__restrict__ pcodes,
                                                    const uint8_t *__restrict__ pflags,
@@ -357,6 +401,19 @@ __global__ __launch_bounds__(kLinWG) void k_linear(const int8_t *__restrict__ xq
     // the last two steps have nothing left to load / to decode: peeled, so that
     // the steady-state body is free of branches
     int kt = 0;
+    // Steady state, two steps per trip so that the two register stages swap roles
+    // instead of being copied; every step loaded here lies wholly below K.
+    const LinOffsets<kBits> offs = lin_offsets<kBits>(M, K, N, row0, col0);
+    const int8_t *a_base = xq + row0 * K;                                   // + k0
+    const uint8_t *code_base = pcodes + ((col0 * K) >> 4) * (2 * kBits);    // + (k0 / 16) * 2b
+    const uint8_t *flag_base = pflags + ((col0 * K) >> 3);                  // + k0 / 8
+    for (; kt + 4 < steps; kt += 2) {
+        const long long k2 = (long long)(kt + 2) * kLinBK, k3 = k2 + kLinBK;
+        lin_load_whole<kBits>(far, offs, a_base + k2, code_base + (k2 >> 4) * (2 * kBits), flag_base + (k2 >> 3));
+        lin_step<kBits, true>(acc, near, 4, a_lane, b_lane, swz, half, sA[0], sB[0], 0);
+        lin_load_whole<kBits>(near, offs, a_base + k3, code_base + (k3 >> 4) * (2 * kBits), flag_base + (k3 >> 3));
+        lin_step<kBits, true>(acc, far, 4, a_lane, b_lane, swz, half, sA[0], sB[0], 1);
+    }
     for (; kt + 2 < steps; ++kt) {
         lin_load<kBits>(far, xq, M, K, pcodes, pflags, N, row0, col0, (long long)(kt + 2) * kLinBK,
                         valid(kt + 2));
