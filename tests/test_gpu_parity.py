@@ -104,6 +104,24 @@ def test_per_tensor(P, shape, n, bits):
     run_both(P, w, bits, n, synth.PER_TENSOR, f"per-tensor {shape}")
 
 
+@pytest.mark.parametrize("K", [1, 5, 8, 9, 16, 17])
+@pytest.mark.parametrize("n", [7, 100, 1000, 2049])
+def test_tiny_channels(P, K, n):
+    """Groups of at most 16 elements (depthwise 3x3 filters have 9) take a path of their own in
+    the search kernel; many of them, so that units hold several tiles, and candidate counts on
+    both sides of one workgroup per tile (n <= 1024) and of workgroups shared by several units
+    (n <= 512).  K = 17 is the first length on the general path."""
+    rng = np.random.default_rng(100 * K + n)
+    C = 2500 if n <= 1000 else 300
+    w = (rng.laplace(0, 0.05, size=(C, K)) * np.exp(rng.normal(0, 1, size=(C, 1)))).astype(np.float32)
+    w[3] = 0.0                                   # an all-zero group
+    w[5, 0] = np.float32(0.7)                    # equal magnitudes
+    w[5, 1:] = np.float32(-0.7)
+    run_both(P, w, 4, n, synth.PER_CHANNEL, f"tiny K={K} n={n}")
+    if K <= 8:
+        run_both(P, w[:2], 3, n, synth.PER_TENSOR, f"tiny per-tensor K={K} n={n}")
+
+
 def test_long_channels_split_into_tiles(P):
     rng = np.random.default_rng(77)
     w = rng.laplace(0, 0.02, size=(3, 30011)).astype(np.float32)
