@@ -10,6 +10,11 @@ namespace pwlq {
 // half-to-even, saturated) with the piece's parameters selected once per
 // element instead of two evaluations selected afterwards; the centre value
 // code*s1 is written fma(code, s1, +0), which rounds the same product.
+// kHat = false: the dequantized value is not wanted.  The sign bit of a code is set for a
+// negative weight whose value is not zero, and the value step*code + offset is zero exactly
+// when the code is 0 and the offset (0 in the centre, p in the tail) is 0, so the code and
+// the flag do not need the value at all.
+template <bool kHat = true>
 __device__ inline void emit_one(const Pieces &q, int bits, float w, uint8_t &code_out,
                                 uint8_t &flag_out, float &hat_out)
 {
@@ -18,14 +23,19 @@ __device__ inline void emit_one(const Pieces &q, int bits, float w, uint8_t &cod
     const float z = tail ? q.p : 0.0f;
     const float x = a - z;                      // a - 0 is a
     const float inv = tail ? q.i2 : q.i1;
-    const float s = tail ? q.s2 : q.s1;
-    const float top = tail ? q.m : q.p;
     float code = rintf(x * inv);
     code = (code > q.L) ? q.L : code;
-    float v = __builtin_fmaf(code, s, z);
-    v = (code == q.L) ? top : v;
-    const bool neg = (w < 0.0f) && (v > 0.0f);
-    hat_out = neg ? -v : v;
+    bool neg;
+    if (kHat) {
+        const float s = tail ? q.s2 : q.s1;
+        const float top = tail ? q.m : q.p;
+        float v = __builtin_fmaf(code, s, z);
+        v = (code == q.L) ? top : v;
+        neg = (w < 0.0f) && (v > 0.0f);
+        hat_out = neg ? -v : v;
+    } else {
+        neg = (w < 0.0f) && (code > 0.0f || (tail && q.p > 0.0f));
+    }
     flag_out = tail ? 1 : 0;
     code_out = (uint8_t)((int)code | ((neg ? 1 : 0) << (bits - 1)));
 }
@@ -243,7 +253,8 @@ __global__ __launch_bounds__(kEmitChunk / kPackPer) void k_emit_packed(Tables tb
 #pragma unroll
             for (int x = 0; x < kPackPer; ++x) {
                 uint8_t c, f;
-                emit_one(q, bits, wv[x], c, f, hv[x]);
+                if (kPackPer == 16) emit_one<false>(q, bits, wv[x], c, f, hv[x]);     // launched without w_hat
+                else emit_one<true>(q, bits, wv[x], c, f, hv[x]);
                 cw[x >> 3] |= (unsigned long long)c << ((x & 7) * bits);
                 fbits |= (unsigned)f << x;
             }
