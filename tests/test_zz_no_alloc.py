@@ -84,3 +84,40 @@ def test_static_scratch_rejects_what_does_not_fit(P):
     with pytest.raises(P.PwlqError) as e:
         P.search_static(wd, 9, n)
     assert e.value.status == 1
+
+
+def test_static_scratch_inside_a_graph(P):
+    """What the entry point is for: recorded once into a HIP graph (where nothing may
+    allocate) and replayed on new contents; every replay against an eager pwlq_search."""
+    import torch
+    rng = np.random.default_rng(21)
+    shape, bits, n = (96, 320), 4, 200
+    wd = torch.from_numpy(rng.laplace(0, 0.05, size=shape).astype(np.float32)).cuda()
+    out = P.alloc_search_outputs(shape[0], wd.device)
+    P.search_static(wd, bits, n, out=out)            # first call on this device: outside the capture
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        P.search_static(wd, bits, n, out=out)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        P.search_static(wd, bits, n, out=out)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        w = (rng.standard_normal(shape) * np.exp(rng.normal(-3, 1))).astype(np.float32)
+        wd.copy_(torch.from_numpy(w))                # eager work between the replays
+        for v in out.values():
+            v.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = {k: v.clone() for k, v in out.items()}
+        eager = P.search(wd, bits, n)
+        torch.cuda.synchronize()
+        for k in ("k_star", "p_star", "m", "mse"):
+            assert torch.equal(got[k], eager[k]), f"replay {rep}: {k} differs from pwlq_search"
+    assert_search_matches({k: v.cpu().numpy() for k, v in got.items()},
+                          R.search(w, bits, n, want_curve=True), "static scratch, last replay")
