@@ -201,7 +201,8 @@ def main() -> int:
     ks = float(np.mean(k_search_ms))
     emit_ms = float(np.mean(k_emit_ms))
     tag = f"workload{wl.index}" + (f"_only_k{args.only_k}" if args.only_k else "")
-    valu, traffic, static_src = _static_counters(tag, pwlq.kernel_name(0))
+    search_kernel = pwlq.last_search_kernel()       # k_search; k_small for a call that is one fused launch
+    valu, traffic, static_src = _static_counters(tag, search_kernel)
     fresh = valu is not None and static_src["executed"]["matches_this_build"]
     # Lane-instructions of the dominant kernel per launch.  Executed: SQ_INSTS_VALU x 64 of the
     # committed counter run of this workload, used only while the kernel sources are the
@@ -238,7 +239,7 @@ def main() -> int:
             "search_evals_per_s": evals / (float(np.mean(search_ms)) * 1e-3),
         },
         "roofline": {
-            "kernel": pwlq.kernel_name(0),
+            "kernel": search_kernel,
             "bound": "alu",
             "achieved": achieved / 1e12,
             "peak": PEAK_LANE_OPS / 1e12,

@@ -31,6 +31,11 @@ double pwlq_profile_last_ms(int role);
  * back = 1 the one before, up to the last 64 recorded launches; -1 beyond. */
 double pwlq_profile_ms(int role, int back);
 
+/* Name of the candidate-evaluation kernel that the calling thread's last search launched
+ * (role 0 of the event timing): "k_search", or "k_small" for a call small enough to be one
+ * fused launch, or "k_fast" for a fast search. */
+const char *pwlq_last_search_kernel(void);
+
 /* Name of the library's kernels as they appear in a kernel trace, by role:
  * 0 search (dominant), 1 quantize, 2 prefix-sum evaluation, 3 integer inner
  * product.  Returns NULL for other roles. */

@@ -5,6 +5,7 @@
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <numeric>
@@ -25,6 +26,7 @@ using namespace pwlq;
 
 thread_local char g_error[512] = "";
 thread_local long long g_last_tiles = 0, g_last_groups = 0, g_last_units = 0;
+thread_local const char *g_last_search_kernel = "k_search";
 
 int fail(int status, const char *fmt, ...)
 {
@@ -362,6 +364,32 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
     double *gsum = (double *)(ws + pl.off_gsum);
 
     const int NT = (int)pl.n_tiles;
+    // A call too small to fill the chip: everything for a group in one workgroup, one launch.
+    {
+        int longest_any = 0;
+        long long evals = 0;
+        for (const TensorRec &r : pl.recs) {
+            longest_any = std::max(longest_any, r.tile_len);
+            evals += (long long)r.ntiles * r.tile_len * n_cand;
+        }
+        // PWLQ_SMALL_CALL_TILES (read once): another limit on the tiles, for measurements of the crossover
+        static const int small_call_tiles = [] {
+            const char *e = getenv("PWLQ_SMALL_CALL_TILES");
+            return e ? atoi(e) : kSmallCallTiles;
+        }();
+        if (!fast && pl.n_mgroups == 0 && NT <= small_call_tiles && evals <= kSmallCallEvals &&
+            longest_any <= kSmallLen && n_cand <= kSmallCand) {
+            profile_mark(0, stream);
+            k_small<<<NT, kSmallWG, 0, stream>>>(tb, n_cand, pl.nblk, bits, p_star, m_out, k_star, mse);
+            profile_mark(1, stream);
+            g_last_tiles = pl.n_tiles;
+            g_last_groups = pl.n_groups;
+            g_last_units = pl.n_tiles;
+            g_last_search_kernel = "k_small";
+            return launch_status("search launch");
+        }
+    }
+    g_last_search_kernel = fast ? "k_fast" : "k_search";
     if (pl.n_mgroups > 0) k_tile_absmax<<<NT, kWG, 0, stream>>>(tb, tile_max);
     int longest = 0, longest_fast = 0, fast_tiles = 0;
     for (const TensorRec &r : pl.recs) {
@@ -949,6 +977,8 @@ void pwlq_last_search_shape(int64_t *n_tiles, int64_t *n_groups, int64_t *n_unit
     if (n_groups) *n_groups = g_last_groups;
     if (n_units) *n_units = g_last_units;
 }
+
+const char *pwlq_last_search_kernel(void) { return g_last_search_kernel; }
 
 const char *pwlq_kernel_name(int role)
 {

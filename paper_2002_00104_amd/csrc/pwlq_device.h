@@ -23,6 +23,8 @@ constexpr int kSmallTile = 1024;  // tiles up to this length get one wavefront e
 constexpr int kSmallPer = kSmallTile / 64;
 constexpr int kTinyTile = 16;     // tiles up to this length are two vectors: evaluated without offsets, loads one tile ahead
 constexpr int kTinyUnit = 32;     // ... and batched up to this many per unit
+constexpr int kSmallCallTiles = 256;    // a search of at most this many short single-tile groups (one per CU) ...
+constexpr long long kSmallCallEvals = 50000000;   // ... and evaluations is one fused launch (measured crossover)
 constexpr int kUnitElems = 4096;  // small tiles are batched up to about this many elements
 constexpr int kMinUnits = 4096;   // ... unless that would leave fewer search units than this
 constexpr int kEmitChunk = 2048;  // elements per workgroup of the quantize kernel (4096 and 8192: 12-45 % slower on a 25 M-element model)

@@ -13,6 +13,11 @@
 //                  code and binary64 error; argmin for single-tile groups
 //   k_final        argmin for groups spread over several tiles
 //
+// A call too small to fill the chip (at most kSmallCallTiles single-tile groups
+// of at most 1024 elements, at most 1024 candidates and kSmallCallEvals
+// evaluations in all) runs k_small instead: all of the above for one group
+// inside one workgroup, one launch.
+//
 // and of one quantize call:  k_emit (HBM bound).
 //
 // The analytic selectors run k_stats (per-tile max, sum of squares, sum of
@@ -27,3 +32,4 @@
 #include "pwlq_select.h"
 #include "pwlq_fast.h"
 #include "pwlq_linear.h"
+#include "pwlq_small.h"

@@ -31,7 +31,7 @@ EXPORTS = (
     "pwlq_mse_workspace_bytes", "pwlq_mse_list_workspace_bytes", "pwlq_mse", "pwlq_mse_list",
     "pwlq_linear_workspace_bytes", "pwlq_linear_i8",
     "pwlq_last_error", "pwlq_last_search_shape", "pwlq_profile_enable",
-    "pwlq_profile_last_ms", "pwlq_profile_ms", "pwlq_kernel_name",
+    "pwlq_profile_last_ms", "pwlq_profile_ms", "pwlq_kernel_name", "pwlq_last_search_kernel",
 )
 
 
@@ -116,6 +116,8 @@ def _load() -> ctypes.CDLL:
     lib.pwlq_profile_ms.argtypes = [ci, ci]
     lib.pwlq_kernel_name.restype = ctypes.c_char_p
     lib.pwlq_kernel_name.argtypes = [ci]
+    lib.pwlq_last_search_kernel.restype = ctypes.c_char_p
+    lib.pwlq_last_search_kernel.argtypes = []
     return lib
 
 
@@ -462,6 +464,10 @@ def last_search_shape():
     a, b, c = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
     lib.pwlq_last_search_shape(ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
     return dict(tiles=a.value, groups=b.value, units=c.value)
+
+
+def last_search_kernel() -> str:
+    return lib.pwlq_last_search_kernel().decode()
 
 
 def kernel_name(role: int) -> Optional[str]:

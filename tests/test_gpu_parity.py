@@ -202,6 +202,37 @@ def test_non_finite_groups(P):
     run_both(P, w2, 4, 50, synth.PER_TENSOR, "non-finite per-tensor")
 
 
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_special_groups_on_both_search_paths(P, bits):
+    """A call of up to 256 short groups is one fused launch (one workgroup per group); larger
+    calls partition, evaluate and refine in separate launches.  The same degenerate and
+    non-finite groups through both: once as they are, once repeated beyond 256 groups."""
+    rng = np.random.default_rng(bits)
+    w = np.zeros((10, 100), np.float32)
+    w[1, 40] = -0.5
+    w[2, :] = 0.25
+    w[2, ::2] *= -1
+    w[3, :50] = 1.0
+    w[3, 50:] = -0.125
+    w[4, :] = np.linspace(-1, 1, 100)
+    w[5, :] = rng.standard_normal(100).astype(np.float32) ** 3
+    w[6, :] = rng.standard_normal(100)
+    w[6, 7] = np.inf
+    w[7, :] = rng.standard_normal(100)
+    w[7, 0] = np.nan
+    w[8, :] = np.round(rng.standard_normal(100) * 2) / 2
+    w[9, :] = rng.laplace(0, 0.05, 100)
+    for n in (100, 1000):
+        run_both(P, w, bits, n, synth.PER_CHANNEL, f"special groups, fused launch, n={n}")
+        assert P.last_search_kernel() != "k_small"            # the last call of run_both was the fast search
+        P.search(__import__("torch").from_numpy(w).cuda(), bits, n)
+        assert P.last_search_kernel() == "k_small"
+        big = np.tile(w, (30, 1))
+        run_both(P, big, bits, n, synth.PER_CHANNEL, f"special groups, separate launches, n={n}")
+        P.search(__import__("torch").from_numpy(big).cuda(), bits, n)
+        assert P.last_search_kernel() == "k_search"
+
+
 def test_out_of_range_values_saturate(P):
     import torch
     w = np.array([[2.0, -3.0, 1.5, 0.1, -0.4]], np.float32)

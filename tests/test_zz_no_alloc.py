@@ -91,7 +91,7 @@ def test_static_scratch_inside_a_graph(P):
     allocate) and replayed on new contents; every replay against an eager pwlq_search."""
     import torch
     rng = np.random.default_rng(21)
-    shape, bits, n = (96, 320), 4, 200
+    shape, bits, n = (600, 320), 4, 200          # more than 256 groups: the launches that use the scratch
     wd = torch.from_numpy(rng.laplace(0, 0.05, size=shape).astype(np.float32)).cuda()
     out = P.alloc_search_outputs(shape[0], wd.device)
     P.search_static(wd, bits, n, out=out)            # first call on this device: outside the capture
@@ -106,6 +106,7 @@ def test_static_scratch_inside_a_graph(P):
     with torch.cuda.graph(g):
         P.search_static(wd, bits, n, out=out)
     torch.cuda.synchronize()
+    assert P.last_search_kernel() == "k_search"
     for rep in range(3):
         w = (rng.standard_normal(shape) * np.exp(rng.normal(-3, 1))).astype(np.float32)
         wd.copy_(torch.from_numpy(w))                # eager work between the replays
