@@ -264,6 +264,10 @@ int pwlq_mse_list(const pwlq_tensor_desc *desc, int n_tensors, int bits, int mod
  * Section 4.
  *   y    device [M, N] binary32, row-major
  *   acc  device [3, M, N] int32 receiving A1, A2, A3, or NULL
+ * With acc NULL the library may form A1 + L A3 as one integer sum (p = s1 L, so
+ * s1 A1 + p A3 = s1 (A1 + L A3); L sigma is an int8 like any code) and issue two
+ * matrix products per weight instead of three; y then differs from the
+ * three-sum form by binary32 rounding only.
  * Requirements: K a multiple of 16; xq and packed_codes 16-byte aligned,
  * packed_flags 2-byte aligned; K * 128 * L below 2^31.  Workspace: device,
  * 256-byte aligned, pwlq_linear_workspace_bytes(N) bytes.

@@ -681,7 +681,10 @@ int run_linear(const int8_t *xq, int64_t M, int64_t K, float s_x, float z_x,
     if (((uintptr_t)workspace & 255) != 0) return fail(PWLQ_EWORKSPACE, "workspace is not 256-byte aligned");
     if (workspace_bytes < need)
         return fail(PWLQ_EWORKSPACE, "workspace holds %zu bytes, %zu needed", workspace_bytes, need);
-    const long long tiles_m = (M + kLinBM - 1) / kLinBM, tiles_n = (N + kLinBN - 1) / kLinBN;
+    // the three sums apart only when the caller asks for them; else the folded form
+    static const bool never_fold = getenv("PWLQ_LINEAR_THREE_PLANES") != nullptr;
+    const int planes = (acc || never_fold) ? 3 : 2;
+    const long long tiles_m = (M + lin_bm(planes) - 1) / lin_bm(planes), tiles_n = (N + kLinBN - 1) / kLinBN;
     const long long tn_per_xcd = (tiles_n + 7) / 8;
     const long long wgs = 8 * tn_per_xcd * tiles_m;
     if (wgs > 0x7fffffffLL) return fail(PWLQ_EINVAL, "grid too large");
@@ -693,10 +696,14 @@ int run_linear(const int8_t *xq, int64_t M, int64_t K, float s_x, float z_x,
         k_linear_wsum<B><<<wsum_wgs, kLinWG, 0, stream>>>(packed_codes, packed_flags, N, K, p, m,  \
                                                           wconst);                                 \
         profile_mark(6, stream);                                                                   \
-        k_linear<B><<<(unsigned)wgs, kLinWG, 0, stream>>>(xq, M, K, s_x, z_x, packed_codes,        \
-                                                         packed_flags, N, p, m, wconst, y, acc,    \
-                                                         (int)tiles_m, (int)tiles_n,               \
-                                                         (int)tn_per_xcd);                         \
+        if (planes == 3)                                                                           \
+            k_linear<B, 3><<<(unsigned)wgs, kLinWG, 0, stream>>>(                                  \
+                xq, M, K, s_x, z_x, packed_codes, packed_flags, N, p, m, wconst, y, acc,           \
+                (int)tiles_m, (int)tiles_n, (int)tn_per_xcd);                                      \
+        else                                                                                       \
+            k_linear<B, 2><<<(unsigned)wgs, kLinWG, 0, stream>>>(                                  \
+                xq, M, K, s_x, z_x, packed_codes, packed_flags, N, p, m, wconst, y, nullptr,       \
+                (int)tiles_m, (int)tiles_n, (int)tn_per_xcd);                                      \
         profile_mark(7, stream);                                                                   \
         break;
     switch (bits) {
