@@ -396,7 +396,7 @@ def main() -> int:
         if not args.no_linear:
             Ml, Kl, Nl, bl = 4096, 4096, 4096, 4
             gen = torch.Generator(device="cuda").manual_seed(7)
-            u01 = torch.rand((Nl, Kl), generator=gen, device="cuda") - 0.5
+            u01 = (torch.rand((Nl, Kl), generator=gen, device="cuda") - 0.5).clamp_(-0.4999999, 0.4999999)
             wlin = (-0.02 * torch.sign(u01) * torch.log1p(-2.0 * u01.abs())).contiguous()   # Laplace(0, 0.02)
             sl = pwlq.search(wlin, bl, 100, fast=True)
             pc, pf, _ = pwlq.quantize_packed(wlin, bl, sl["p_star"], sl["m"], want_w_hat=False)
