@@ -1,8 +1,9 @@
 /*
- * pwlq_bench.h - measurement aids of libpwlq.  Not part of the quantization
- * interface (pwlq.h): nothing here changes what a call computes.  Used by the
- * benchmark driver to time single kernels inside a call and to name them in a
- * kernel trace.
+ * pwlq_bench.h - measurement and test aids of libpwlq.  Not part of the
+ * quantization interface (pwlq.h): nothing here changes what a call computes.
+ * Used by the benchmark driver to time single kernels inside a call and to name
+ * them in a kernel trace, and by the tests to choose between two routes to the
+ * same result.
  */
 #ifndef PWLQ_BENCH_H
 #define PWLQ_BENCH_H
@@ -35,6 +36,14 @@ double pwlq_profile_ms(int role, int back);
  * (role 0 of the event timing): "k_search", or "k_small" for a call small enough to be one
  * fused launch, or "k_fast" for a fast search. */
 const char *pwlq_last_search_kernel(void);
+
+/* Test and measurement aid.  A search call of at most this many groups (all of at
+ * most 1024 elements, at most 1024 candidates) runs as one fused launch, one
+ * workgroup per group; larger calls partition, evaluate and refine in separate
+ * launches.  Both routes meet the same definition of the result; this sets the
+ * limit (0: never the fused launch; negative: the default, 256) so that one input
+ * can be put through both, and returns the limit it replaces.  Process-wide. */
+int pwlq_set_small_call_tiles(int tiles);
 
 /* Name of the library's kernels as they appear in a kernel trace, by role:
  * 0 search (dominant), 1 quantize, 2 prefix-sum evaluation, 3 integer inner

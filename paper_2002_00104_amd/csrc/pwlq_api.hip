@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <atomic>
 #include <mutex>
 #include <numeric>
 #include <vector>
@@ -321,6 +322,17 @@ int fast_min_len(int bits)
     return 16 * (2 * L + 1) + 64;
 }
 
+// Largest number of groups a search call may have and still run as one fused launch
+// (PWLQ_SMALL_CALL_TILES overrides the default once; pwlq_set_small_call_tiles at any time).
+std::atomic<int> &small_call_tiles()
+{
+    static std::atomic<int> v([] {
+        const char *e = getenv("PWLQ_SMALL_CALL_TILES");
+        return e ? atoi(e) : kSmallCallTiles;
+    }());
+    return v;
+}
+
 int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand, int mode,
                float *p_star, float *m_out, int32_t *k_star, double *mse, void *workspace,
                size_t workspace_bytes, void *stream_v, bool fast = false)
@@ -372,12 +384,7 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
             longest_any = std::max(longest_any, r.tile_len);
             evals += (long long)r.ntiles * r.tile_len * n_cand;
         }
-        // PWLQ_SMALL_CALL_TILES (read once): another limit on the tiles, for measurements of the crossover
-        static const int small_call_tiles = [] {
-            const char *e = getenv("PWLQ_SMALL_CALL_TILES");
-            return e ? atoi(e) : kSmallCallTiles;
-        }();
-        if (!fast && pl.n_mgroups == 0 && NT <= small_call_tiles && evals <= kSmallCallEvals &&
+        if (!fast && pl.n_mgroups == 0 && NT <= small_call_tiles().load() && evals <= kSmallCallEvals &&
             longest_any <= kSmallLen && n_cand <= kSmallCand) {
             profile_mark(0, stream);
             k_small<<<NT, kSmallWG, 0, stream>>>(tb, n_cand, pl.nblk, bits, p_star, m_out, k_star, mse);
@@ -983,6 +990,11 @@ void pwlq_last_search_shape(int64_t *n_tiles, int64_t *n_groups, int64_t *n_unit
     if (n_tiles) *n_tiles = g_last_tiles;
     if (n_groups) *n_groups = g_last_groups;
     if (n_units) *n_units = g_last_units;
+}
+
+int pwlq_set_small_call_tiles(int tiles)
+{
+    return small_call_tiles().exchange(tiles < 0 ? kSmallCallTiles : tiles);
 }
 
 const char *pwlq_last_search_kernel(void) { return g_last_search_kernel; }

@@ -32,6 +32,7 @@ EXPORTS = (
     "pwlq_linear_workspace_bytes", "pwlq_linear_i8",
     "pwlq_last_error", "pwlq_last_search_shape", "pwlq_profile_enable",
     "pwlq_profile_last_ms", "pwlq_profile_ms", "pwlq_kernel_name", "pwlq_last_search_kernel",
+    "pwlq_set_small_call_tiles",
 )
 
 
@@ -118,6 +119,8 @@ def _load() -> ctypes.CDLL:
     lib.pwlq_kernel_name.argtypes = [ci]
     lib.pwlq_last_search_kernel.restype = ctypes.c_char_p
     lib.pwlq_last_search_kernel.argtypes = []
+    lib.pwlq_set_small_call_tiles.restype = ctypes.c_int
+    lib.pwlq_set_small_call_tiles.argtypes = [ctypes.c_int]
     return lib
 
 
@@ -468,6 +471,12 @@ def last_search_shape():
 
 def last_search_kernel() -> str:
     return lib.pwlq_last_search_kernel().decode()
+
+
+def set_small_call_tiles(tiles: int) -> int:
+    """Most groups a search call may have to run as one fused launch (0: never; negative:
+    the default).  Returns the limit it replaces."""
+    return int(lib.pwlq_set_small_call_tiles(int(tiles)))
 
 
 def kernel_name(role: int) -> Optional[str]:

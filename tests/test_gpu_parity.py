@@ -42,6 +42,16 @@ def run_both(P, w, bits, n, mode, what):
     g = to_np(g)
     r = R.search(w, bits, n, mode, want_curve=True)
     stats = assert_search_matches(g, r, what)
+    if P.last_search_kernel() == "k_small":
+        # small enough for the fused launch: the same input through the separate launches too
+        before = P.set_small_call_tiles(0)
+        try:
+            g2 = P.search(wd, bits, n, mode)
+            torch.cuda.synchronize()
+            assert P.last_search_kernel() == "k_search"
+        finally:
+            P.set_small_call_tiles(before)
+        assert_search_matches(to_np(g2), r, what + " (separate launches)")
     # the prefix-sum search must meet the same definition
     gf = P.search(wd, bits, n, mode, fast=True)
     torch.cuda.synchronize()
@@ -271,6 +281,22 @@ def _list_case(P, tensors, bits, n, mode, what, check_groups=None, packed=False)
     out = P.search_list(tl, bits, n)
     torch.cuda.synchronize()
     say(f"  search done, shape {P.last_search_shape()}")
+    if P.last_search_kernel() == "k_small":
+        # small enough for the fused launch: the separate launches must give the same result
+        # (both refine the same candidates exactly, in binary64, in the same order)
+        before = P.set_small_call_tiles(0)
+        try:
+            out2 = to_np(P.search_list(tl, bits, n))
+            torch.cuda.synchronize()
+            assert P.last_search_kernel() == "k_search"
+        finally:
+            P.set_small_call_tiles(before)
+        g1 = to_np(out)
+        np.testing.assert_array_equal(g1["k_star"], out2["k_star"])
+        np.testing.assert_array_equal(g1["p_star"], out2["p_star"])
+        np.testing.assert_array_equal(g1["m"], out2["m"])
+        np.testing.assert_allclose(g1["mse"], out2["mse"], rtol=1e-12, atol=0)
+        say("  fused launch and separate launches agree")
     fast = to_np(P.search_list(tl, bits, n, fast=True))
     torch.cuda.synchronize()
     say("  fast search done")
