@@ -637,8 +637,9 @@ int run_select(const pwlq_tensor_desc *desc, int n_tensors, int mode, int select
     float *tile_max = (float *)(ws + pl.off_stat_max);
     double *tile_s2 = (double *)(ws + pl.off_stat_s2);
     double *tile_s1 = (double *)(ws + pl.off_stat_s1);
-    k_stats<<<(int)pl.n_tiles, kWG, 0, stream>>>(tb, tile_max, tile_s2, tile_s1);
-    k_select<<<(int)((pl.n_groups + kWG - 1) / kWG), kWG, 0, stream>>>(
+    k_stats<<<(int)((pl.n_tiles + kWaves - 1) / kWaves), kWG, 0, stream>>>(tb, (int)pl.n_tiles, tile_max, tile_s2,
+                                                                      tile_s1);
+    k_select<<<(int)((pl.n_groups + kSelectWG - 1) / kSelectWG), kSelectWG, 0, stream>>>(
         tb, (int)pl.n_groups, selector, tile_max, tile_s2, tile_s1, p_out, m_out);
     return launch_status("select launch");
 }
@@ -660,7 +661,8 @@ int run_mse(const pwlq_tensor_desc *desc, int n_tensors, int bits, int mode, con
     rc = upload_tables(pl, ws, stream, tb);
     if (rc) return rc;
     double *tile_sse = (double *)(ws + pl.off_stat_s2);
-    k_mse_tile<<<(int)pl.n_tiles, kWG, 0, stream>>>(tb, bits, p, m, tile_sse);
+    k_mse_tile<<<(int)((pl.n_tiles + kWaves - 1) / kWaves), kWG, 0, stream>>>(tb, (int)pl.n_tiles, bits, p, m,
+                                                                         tile_sse);
     k_mse_final<<<(int)((pl.n_groups + kWG - 1) / kWG), kWG, 0, stream>>>(tb, (int)pl.n_groups,
                                                                         tile_sse, mse);
     return launch_status("mse launch");

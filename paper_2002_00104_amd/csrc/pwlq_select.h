@@ -20,51 +20,59 @@ __device__ inline int find_tensor_lane(const int *__restrict__ prefix, int nt, i
     return lo;
 }
 
-// Sum over the workgroup in a fixed order, valid in thread 0.
-__device__ inline double block_sum0(double v, double *lds)
-{
-    v = wave_sum(v);
-    if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = v;
-    __syncthreads();
-    double s = lds[0];
-    for (int i = 1; i < kWaves; ++i) s += lds[i];
-    return s;
-}
-
 // ------------------------------------------------------------------- stats
 // Per tile: max|w| (NaN if any element is NaN), sum of w^2 and sum of |w| in
-// binary64.  One workgroup per tile, every element read once.
-__global__ __launch_bounds__(kWG) void k_stats(Tables tb, float *__restrict__ tile_max,
+// binary64.  One wavefront per tile (most tiles are a few hundred elements: a
+// workgroup per tile spends its time on the reductions and the barrier), every
+// element read once, four loads in flight per lane with a partial sum each,
+// added in a fixed order.
+constexpr int kStatUnroll = 4;
+
+__global__ __launch_bounds__(kWG) void k_stats(Tables tb, int n_tiles, float *__restrict__ tile_max,
                                                double *__restrict__ tile_s2,
                                                double *__restrict__ tile_s1)
 {
-    __shared__ float red[kWaves];
-    __shared__ int redbad[kWaves];
-    __shared__ double lds2[kWaves], lds1[kWaves];
+    const int slot = uni((int)(blockIdx.x * kWaves + (threadIdx.x >> 6)));
+    if (slot >= n_tiles) return;
     int t;
     TensorRec r;
-    TileInfo ti = tile_of(tb, blockIdx.x, r, t);
+    TileInfo ti = tile_of(tb, slot, r, t);
+    const int lane = threadIdx.x & 63;
     float mx = 0.0f;
     int bad = 0;
-    double s2 = 0.0, s1 = 0.0;
-    for (int i = threadIdx.x; i < ti.len; i += kWG) {
+    double s2[kStatUnroll], s1[kStatUnroll];
+#pragma unroll
+    for (int u = 0; u < kStatUnroll; ++u) s2[u] = s1[u] = 0.0;
+    int i = lane;
+    for (; i + 64 * (kStatUnroll - 1) < ti.len; i += 64 * kStatUnroll) {
+        float a[kStatUnroll];
+#pragma unroll
+        for (int u = 0; u < kStatUnroll; ++u) a[u] = fabsf(ti.src[i + 64 * u]);
+#pragma unroll
+        for (int u = 0; u < kStatUnroll; ++u) {
+            bad |= (a[u] != a[u]);
+            mx = fmaxf(mx, a[u]);
+            const double d = (double)a[u];
+            s2[u] += d * d;
+            s1[u] += d;
+        }
+    }
+    for (; i < ti.len; i += 64) {
         const float a = fabsf(ti.src[i]);
         bad |= (a != a);
         mx = fmaxf(mx, a);
         const double d = (double)a;
-        s2 += d * d;
-        s1 += d;
+        s2[0] += d * d;
+        s1[0] += d;
     }
+    const double t2 = wave_sum((s2[0] + s2[1]) + (s2[2] + s2[3]));
+    const double t1 = wave_sum((s1[0] + s1[1]) + (s1[2] + s1[3]));
     mx = wave_max(mx);
     bad = wave_or(bad);
-    if ((threadIdx.x & 63) == 0) { red[threadIdx.x >> 6] = mx; redbad[threadIdx.x >> 6] = bad; }
-    s2 = block_sum0(s2, lds2);
-    s1 = block_sum0(s1, lds1);
-    if (threadIdx.x == 0) {
-        for (int i = 1; i < kWaves; ++i) { mx = fmaxf(mx, red[i]); bad |= redbad[i]; }
+    if (lane == 0) {
         tile_max[t] = bad ? __builtin_nanf("") : mx;
-        tile_s2[t] = s2;
-        tile_s1[t] = s1;
+        tile_s2[t] = t2;
+        tile_s1[t] = t1;
     }
 }
 
@@ -129,14 +137,16 @@ __device__ inline double solve_breakpoint(double m, double scale, bool laplace, 
 // scale about zero (sigma^2 = mean w^2, beta = mean |w|) and select p.
 // selector 0: Section 5.1's logarithmic fit, p = sigma ln(0.8614 m/sigma + 0.6079);
 // selector 1: Eq.11 for the truncated Gaussian; 2: for the truncated Laplacian.
-__global__ __launch_bounds__(kWG) void k_select(Tables tb, int n_groups, int selector,
+constexpr int kSelectWG = 64;     // one wavefront per workgroup: a few ten thousand groups reach every CU
+
+__global__ __launch_bounds__(kSelectWG) void k_select(Tables tb, int n_groups, int selector,
                                                 const float *__restrict__ tile_max,
                                                 const double *__restrict__ tile_s2,
                                                 const double *__restrict__ tile_s1,
                                                 float *__restrict__ p_out,
                                                 float *__restrict__ m_out)
 {
-    const int g = blockIdx.x * kWG + threadIdx.x;
+    const int g = blockIdx.x * kSelectWG + threadIdx.x;
     if (g >= n_groups) return;
     const int tensor = (tb.nt == 1) ? 0 : find_tensor_lane(tb.group_prefix, tb.nt, g);
     const TensorRec &r = (tb.nt == 1) ? tb.one : tb.recs[tensor];
@@ -172,22 +182,35 @@ __global__ __launch_bounds__(kWG) void k_select(Tables tb, int n_groups, int sel
 
 // --------------------------------------------------------------------- mse
 // Squared error of Eq.3 over one tile with the group's (m, p): canonical
-// binary32 code, binary64 error, fixed summation order.
-__global__ __launch_bounds__(kWG) void k_mse_tile(Tables tb, int bits,
+// binary32 code, binary64 error, fixed summation order.  One wavefront per
+// tile, as in k_stats.
+__global__ __launch_bounds__(kWG) void k_mse_tile(Tables tb, int n_tiles, int bits,
                                                   const float *__restrict__ p_in,
                                                   const float *__restrict__ m_in,
                                                   double *__restrict__ tile_sse)
 {
-    __shared__ double lds[kWaves];
+    const int slot = uni((int)(blockIdx.x * kWaves + (threadIdx.x >> 6)));
+    if (slot >= n_tiles) return;
     int t;
     TensorRec r;
-    TileInfo ti = tile_of(tb, blockIdx.x, r, t);
+    TileInfo ti = tile_of(tb, slot, r, t);
     const long long og = r.out_group + ti.group_local;
     const Pieces q = make_pieces(m_in[og], p_in[og], bits);
-    double acc = 0.0;
-    for (int i = threadIdx.x; i < ti.len; i += kWG) acc += exact_error_sq(q, fabsf(ti.src[i]));
-    acc = block_sum0(acc, lds);
-    if (threadIdx.x == 0) tile_sse[t] = acc;
+    const int lane = threadIdx.x & 63;
+    double acc[kStatUnroll];
+#pragma unroll
+    for (int u = 0; u < kStatUnroll; ++u) acc[u] = 0.0;
+    int i = lane;
+    for (; i + 64 * (kStatUnroll - 1) < ti.len; i += 64 * kStatUnroll) {
+        float a[kStatUnroll];
+#pragma unroll
+        for (int u = 0; u < kStatUnroll; ++u) a[u] = fabsf(ti.src[i + 64 * u]);
+#pragma unroll
+        for (int u = 0; u < kStatUnroll; ++u) acc[u] += exact_error_sq(q, a[u]);
+    }
+    for (; i < ti.len; i += 64) acc[0] += exact_error_sq(q, fabsf(ti.src[i]));
+    const double s = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
+    if (lane == 0) tile_sse[t] = s;
 }
 
 __global__ __launch_bounds__(kWG) void k_mse_final(Tables tb, int n_groups,
