@@ -335,8 +335,12 @@ __device__ inline void exact_body(const TensorRec &r, const TileInfo &ti, int t,
     }
 }
 
+// The kernel waits on chains of dependent loads (table, tile, filter row,
+// elements), so wavefronts in flight are what it runs on: the 128-thread
+// variant fits 78 registers, six wavefronts per SIMD, without spilling (the
+// one-wavefront variant spills below 111 and measured slower there).
 template <int kT>
-__global__ __launch_bounds__(kT) void k_exact(Tables tb, int tile_begin, int n, int bits,
+__global__ __launch_bounds__(kT, kT == 128 ? 6 : 1) void k_exact(Tables tb, int tile_begin, int n, int bits,
                                               const float *__restrict__ gm,
                                               const float *__restrict__ sse32,
                                               const int *__restrict__ klist,
