@@ -384,11 +384,13 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
             longest_any = std::max(longest_any, r.tile_len);
             evals += (long long)r.ntiles * r.tile_len * n_cand;
         }
-        if (!fast && pl.n_mgroups == 0 && NT <= small_call_tiles().load() && evals <= kSmallCallEvals &&
+        // (also for a fast search: at this size the fused exhaustive launch is the faster way
+        // to the same result)
+        if (pl.n_mgroups == 0 && NT <= small_call_tiles().load() && evals <= kSmallCallEvals &&
             longest_any <= kSmallLen && n_cand <= kSmallCand) {
-            profile_mark(0, stream);
+            profile_mark(fast ? 4 : 0, stream);
             k_small<<<NT, kSmallWG, 0, stream>>>(tb, n_cand, pl.nblk, bits, p_star, m_out, k_star, mse);
-            profile_mark(1, stream);
+            profile_mark(fast ? 5 : 1, stream);
             g_last_tiles = pl.n_tiles;
             g_last_groups = pl.n_groups;
             g_last_units = pl.n_tiles;

@@ -52,9 +52,15 @@ def run_both(P, w, bits, n, mode, what):
         finally:
             P.set_small_call_tiles(before)
         assert_search_matches(to_np(g2), r, what + " (separate launches)")
-    # the prefix-sum search must meet the same definition
-    gf = P.search(wd, bits, n, mode, fast=True)
-    torch.cuda.synchronize()
+    # the prefix-sum search must meet the same definition (a small call would take the
+    # fused launch here too: the limit is lifted so that the prefix sums run)
+    before = P.set_small_call_tiles(0)
+    try:
+        gf = P.search(wd, bits, n, mode, fast=True)
+        torch.cuda.synchronize()
+        assert P.last_search_kernel() == "k_fast"
+    finally:
+        P.set_small_call_tiles(before)
     assert_search_matches(to_np(gf), r, what + " (fast)")
     # quantize with the oracle's parameters on both sides, so a legitimate
     # near-tie difference in k* cannot leak into the code comparison
@@ -234,7 +240,6 @@ def test_special_groups_on_both_search_paths(P, bits):
     w[9, :] = rng.laplace(0, 0.05, 100)
     for n in (100, 1000):
         run_both(P, w, bits, n, synth.PER_CHANNEL, f"special groups, fused launch, n={n}")
-        assert P.last_search_kernel() != "k_small"            # the last call of run_both was the fast search
         P.search(__import__("torch").from_numpy(w).cuda(), bits, n)
         assert P.last_search_kernel() == "k_small"
         big = np.tile(w, (30, 1))
@@ -297,8 +302,12 @@ def _list_case(P, tensors, bits, n, mode, what, check_groups=None, packed=False)
         np.testing.assert_array_equal(g1["m"], out2["m"])
         np.testing.assert_allclose(g1["mse"], out2["mse"], rtol=1e-12, atol=0)
         say("  fused launch and separate launches agree")
-    fast = to_np(P.search_list(tl, bits, n, fast=True))
-    torch.cuda.synchronize()
+    before = P.set_small_call_tiles(0)          # the prefix sums, also for a small call
+    try:
+        fast = to_np(P.search_list(tl, bits, n, fast=True))
+        torch.cuda.synchronize()
+    finally:
+        P.set_small_call_tiles(before)
     say("  fast search done")
     codes, flags, w_hat = P.quantize_list(tl, bits, out["p_star"], out["m"])
     torch.cuda.synchronize()
