@@ -693,8 +693,7 @@ int run_linear(const int8_t *xq, int64_t M, int64_t K, float s_x, float z_x,
     if (workspace_bytes < need)
         return fail(PWLQ_EWORKSPACE, "workspace holds %zu bytes, %zu needed", workspace_bytes, need);
     // the three sums apart only when the caller asks for them; else the folded form
-    static const bool never_fold = getenv("PWLQ_LINEAR_THREE_PLANES") != nullptr;
-    const int planes = (acc || never_fold) ? 3 : 2;
+    const int planes = acc ? 3 : 2;
     const long long tiles_m = (M + lin_bm(planes) - 1) / lin_bm(planes), tiles_n = (N + kLinBN - 1) / kLinBN;
     const long long tn_per_xcd = (tiles_n + 7) / 8;
     const long long wgs = 8 * tn_per_xcd * tiles_m;
