@@ -84,6 +84,9 @@ def _static_counters(tag: str, kernel: str):
     if rec and kernel in rec.get("kernels", {}):
         k = rec["kernels"][kernel]
         traffic = float(k["read_bytes"]) + float(k["written_bytes"])
+        if "read_bytes_by_request_size" in k:
+            # the L2's read requests priced at their own size (32, 64, 128 bytes) + the writes
+            src["traffic_by_request_size"] = float(k["read_bytes_by_request_size"]) + float(k["written_bytes"])
         src["traffic"] = {"file": f"profiles/hbm_traffic_{tag}.txt", "static": True,
                           "counter": "FETCH_SIZE + WRITE_SIZE per launch, scaled by a plain copy",
                           "kernel_sources_sha16": rec.get("kernel_sources_sha16"),
@@ -278,6 +281,13 @@ def main() -> int:
                               "fused multiply-add); the 157.3 TFLOP/s figure needs packed fused "
                               "multiply-adds, which this build does not use",
             "traffic": traffic,
+            "traffic_by_request_size": static_src.pop("traffic_by_request_size", None),
+            "traffic_note": "traffic: FETCH_SIZE and WRITE_SIZE, each scaled by what it reads for a plain "
+                            "copy.  FETCH_SIZE prices a 128-byte read request at 64 bytes (the copy's "
+                            "factor 2.0) and a 64-byte one at 64, so the scaling doubles the reads of this "
+                            "kernel, whose elements arrive as 64-byte scalar-cache fills; "
+                            "traffic_by_request_size prices every read request of the L2 at its size "
+                            "(TCC_EA0_RDREQ_32B/_64B/_128B) and adds the same writes",
             "algorithmic_bytes": algorithmic_bytes,
             "static_sources": static_src,
             "kernel_sources_sha16": sources_sha16(),
