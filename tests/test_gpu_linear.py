@@ -104,3 +104,18 @@ def test_linear_error_statuses(P):
         P.linear_i8(x, 1.0, 0.0, c[1:], c, 4, 4, p, p)        # misaligned code stream
     assert e.value.status == 1
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("seed", [3, 4])
+def test_random_shapes(P, seed):
+    """Seeded draws of M, K (a multiple of 16), N, bit width and distribution."""
+    rng = np.random.default_rng(seed)
+    worst = 0.0
+    for i in range(60):
+        M = int(np.exp(rng.uniform(0, np.log(700))))
+        K = 16 * int(np.exp(rng.uniform(0, np.log(200))))
+        N = int(np.exp(rng.uniform(0, np.log(400))))
+        bits = int(rng.integers(2, 9))
+        worst = max(worst, case(P, M, K, N, bits, seed=seed * 1000 + i,
+                                dist="laplace" if rng.random() < 0.5 else "normal"))
+    say(f"worst relative error of y over 60 random shapes: {worst:.2e}")
