@@ -512,20 +512,34 @@ int run_search(const pwlq_tensor_desc *desc, int n_tensors, int bits, int n_cand
         k_group_sum<<<(unsigned)group_sum_wgs, kWG, 0, stream>>>(tb, n_cand, sse32, gsum);
         k_flag<<<(int)pl.n_mgroups, kWG, 0, stream>>>(tb, n_cand, gm, gsum, klist);
     }
+    // Single-tile groups only: the short tiles above 512 elements (next in the tile order) join
+    // the two-wavefront launch, so that the one-wavefront launch holds 8 elements per thread
+    // instead of 16 and fits six wavefronts per SIMD like the other.
+    int nt_mid = 0;
+    if (pl.n_mgroups == 0 && nt_large > 0 && nt_small > 0)
+        for (const TensorRec &r : pl.recs)
+            if (r.tile_len <= kSmallTile && r.tile_len > 512) nt_mid += r.ntiles;
     if (nt_large > 0) {
         // single-tile groups only: workgroups of two wavefronts, twice as many in flight (the
         // stage is bound by latency); with groups spread over tiles, where a tile's threads
         // share the evaluation of the group's whole list, four wavefronts measured faster
         if (pl.n_mgroups == 0)
-            k_exact<128><<<nt_large, 128, 0, stream>>>(tb, 0, n_cand, bits, gm, sse32, klist, part64, p_star,
-                                                       m_out, k_star, mse);
+            k_exact<128><<<nt_large + nt_mid, 128, 0, stream>>>(tb, 0, n_cand, bits, gm, sse32, klist, part64,
+                                                                p_star, m_out, k_star, mse);
         else
             k_exact<kWG><<<nt_large, kWG, 0, stream>>>(tb, 0, n_cand, bits, gm, sse32, klist, part64, p_star,
                                                        m_out, k_star, mse);
     }
-    if (nt_small > 0)
-        k_exact<64><<<nt_small, 64, 0, stream>>>(tb, nt_large, n_cand, bits, gm, sse32, klist, part64,
-                                                 p_star, m_out, k_star, mse);
+    if (nt_small > 0) {
+        if (nt_mid > 0) {
+            if (nt_small > nt_mid)
+                k_exact<64, 8><<<nt_small - nt_mid, 64, 0, stream>>>(tb, nt_large + nt_mid, n_cand, bits, gm, sse32,
+                                                                      klist, part64, p_star, m_out, k_star, mse);
+        } else {
+            k_exact<64><<<nt_small, 64, 0, stream>>>(tb, nt_large, n_cand, bits, gm, sse32, klist, part64,
+                                                     p_star, m_out, k_star, mse);
+        }
+    }
     if (pl.n_mgroups > 0)
         k_final<<<(int)pl.n_mgroups, kWG, 0, stream>>>(tb, n_cand, gm, klist, part64, p_star, m_out,
                                                        k_star, mse);

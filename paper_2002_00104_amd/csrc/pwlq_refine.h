@@ -339,8 +339,10 @@ __device__ inline void exact_body(const TensorRec &r, const TileInfo &ti, int t,
 // elements), so wavefronts in flight are what it runs on: the 128-thread
 // variant fits 78 registers, six wavefronts per SIMD, without spilling (the
 // one-wavefront variant spills below 111 and measured slower there).
-template <int kT>
-__global__ __launch_bounds__(kT, kT == 128 ? 6 : 1) void k_exact(Tables tb, int tile_begin, int n, int bits,
+// kMaxPer (one-wavefront variant): the most elements a thread holds, 16 for tiles up to 1024
+// elements, 8 when the launch only sees tiles up to 512 (then 6 wavefronts per SIMD too).
+template <int kT, int kMaxPer = 16>
+__global__ __launch_bounds__(kT, (kT == 128 || (kT == 64 && kMaxPer == 8)) ? 6 : 1) void k_exact(Tables tb, int tile_begin, int n, int bits,
                                               const float *__restrict__ gm,
                                               const float *__restrict__ sse32,
                                               const int *__restrict__ klist,
@@ -364,7 +366,7 @@ __global__ __launch_bounds__(kT, kT == 128 ? 6 : 1) void k_exact(Tables tb, int 
         if (ti.len <= 64) PWLQ_EXACT(1);
         else if (ti.len <= 128) PWLQ_EXACT(2);
         else if (ti.len <= 256) PWLQ_EXACT(4);
-        else if (ti.len <= 512) PWLQ_EXACT(8);
+        else if (ti.len <= 512 || kMaxPer == 8) PWLQ_EXACT(8);
         else if (ti.len <= 640) PWLQ_EXACT(10);
         else PWLQ_EXACT(kSmallPer);
     } else {
