@@ -18,7 +18,14 @@ __global__ __launch_bounds__(kWG) void k_tile_absmax(Tables tb, float *__restric
     if (r.tpg == 1) return;
     float mx = 0.0f;
     int bad = 0;
-    for (int i = threadIdx.x; i < ti.len; i += kWG) {
+    int i = threadIdx.x;
+    for (; i + 3 * kWG < ti.len; i += 4 * kWG) {       // four loads in flight per thread
+        const float a0 = fabsf(ti.src[i]), a1 = fabsf(ti.src[i + kWG]), a2 = fabsf(ti.src[i + 2 * kWG]),
+                    a3 = fabsf(ti.src[i + 3 * kWG]);
+        bad |= (a0 != a0) | (a1 != a1) | (a2 != a2) | (a3 != a3);
+        mx = fmaxf(fmaxf(mx, fmaxf(a0, a1)), fmaxf(a2, a3));
+    }
+    for (; i < ti.len; i += kWG) {
         float a = fabsf(ti.src[i]);
         bad |= (a != a);
         mx = fmaxf(mx, a);

@@ -158,8 +158,15 @@ __device__ inline void exact_tile(const float *__restrict__ src, int len,
                 for (int e = 0; e < kEpt; ++e)
                     if (tid + e * kT < len) acc0 += exact_error_sq(q0, a[e]);
             } else {
-                // four loads in flight per thread: the pass is bound by their latency
+                // eight, then four loads in flight per thread: the pass is bound by their latency
                 int i = tid;
+                for (; i + 7 * kT < len; i += 8 * kT) {
+                    float av[8];
+#pragma unroll
+                    for (int x = 0; x < 8; ++x) av[x] = fabsf(src[i + x * kT]);
+#pragma unroll
+                    for (int x = 0; x < 8; ++x) acc0 += exact_error_sq(q0, av[x]);
+                }
                 for (; i + 3 * kT < len; i += 4 * kT) {
                     const float a0 = fabsf(src[i]), a1 = fabsf(src[i + kT]),
                                 a2 = fabsf(src[i + 2 * kT]), a3 = fabsf(src[i + 3 * kT]);
@@ -182,6 +189,16 @@ __device__ inline void exact_tile(const float *__restrict__ src, int len,
                 }
             } else {
                 int i = tid;
+                for (; i + 7 * kT < len; i += 8 * kT) {
+                    float av[8];
+#pragma unroll
+                    for (int x = 0; x < 8; ++x) av[x] = fabsf(src[i + x * kT]);
+#pragma unroll
+                    for (int x = 0; x < 8; ++x) {
+                        acc0 += exact_error_sq(q0, av[x]);
+                        acc1 += exact_error_sq(q1, av[x]);
+                    }
+                }
                 for (; i + 3 * kT < len; i += 4 * kT) {
                     const float a0 = fabsf(src[i]), a1 = fabsf(src[i + kT]),
                                 a2 = fabsf(src[i + 2 * kT]), a3 = fabsf(src[i + 3 * kT]);
