@@ -41,8 +41,19 @@ __global__ __launch_bounds__(kWG) void k_group_sum(Tables tb, int n,
     const int gl = mg - r.mgroup_base;
     const long long tile0 = r.tile_base + (long long)gl * r.tpg;
     double v = 0.0;
-    if (k0 < n)
-        for (int j = ph; j < r.tpg; j += kSumPhases) v += (double)sse32[(tile0 + j) * n + k0];
+    if (k0 < n) {
+        int j = ph;
+        for (; j + 3 * kSumPhases < r.tpg; j += 4 * kSumPhases) {     // four loads in flight, added in the same order
+            const float x0 = sse32[(tile0 + j) * n + k0], x1 = sse32[(tile0 + j + kSumPhases) * n + k0],
+                        x2 = sse32[(tile0 + j + 2 * kSumPhases) * n + k0],
+                        x3 = sse32[(tile0 + j + 3 * kSumPhases) * n + k0];
+            v += (double)x0;
+            v += (double)x1;
+            v += (double)x2;
+            v += (double)x3;
+        }
+        for (; j < r.tpg; j += kSumPhases) v += (double)sse32[(tile0 + j) * n + k0];
+    }
     part[ph][c] = v;
     __syncthreads();
     if (ph == 0 && k0 < n) {
